@@ -1,0 +1,241 @@
+/*
+ * libcdf - the per-partition layer step of cache-based distributed full-batch GCN
+ * training (CDFGNN), for one AMD MI355X (gfx950).
+ *
+ * One partition owns n_loc vertices ("local rows") and reads n_halo remote
+ * neighbours ("halo rows"). Feature matrices are row-major with local rows first:
+ * Xfull = [ local rows ; halo rows ], (n_loc + n_halo) x dim.
+ *
+ * Conventions for every entry point
+ *  - C ABI. Every pointer is a DEVICE pointer owned by the caller unless the
+ *    parameter comment says "host". The library never allocates or frees device
+ *    memory; scratch comes from the caller's workspace `ws` (size it with
+ *    cdf_workspace_bytes; 256-byte aligned).
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null
+ *    stream) and the call returns without synchronising. Counts produced on the
+ *    device (n_sent) stay on the device; consumers read them there.
+ *  - Row-major matrices carry a leading dimension `ld` in ELEMENTS (ld >= dim).
+ *  - Element type cdf_dtype: fp32, or bf16 storage with fp32 arithmetic.
+ *  - Return value: CDF_OK or a negative cdf_status. Invalid arguments are rejected
+ *    on the host before anything is launched. cdf_last_error() gives a host string.
+ *  - Inputs are assumed finite. Calls sharing a workspace must be ordered on one
+ *    stream; distinct workspaces may run concurrently.
+ *  - n_rows == 0, max_sent == 0 and *n_sent == 0 are valid and do nothing.
+ */
+#ifndef CDF_H
+#define CDF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  CDF_OK = 0,
+  CDF_ERR_INVALID_ARG = -1, /* null / negative / misaligned / ld < dim / non-finite eps */
+  CDF_ERR_UNSUPPORTED = -2, /* dtype, bits, norm or scheme combination not provided */
+  CDF_ERR_WORKSPACE = -3,   /* workspace missing or too small */
+  CDF_ERR_HIP = -4          /* a launch failed; see cdf_last_error() */
+} cdf_status;
+
+typedef enum { CDF_F32 = 0, CDF_BF16 = 1 } cdf_dtype;
+
+/* Row norm of the cache test. LINF is the paper's (Alg. 2, Sec. 4.1). L2 compares
+ * squared sums in fp32 with a fixed summation order: 256 interleaved chains (chain c
+ * takes elements c, c+256, ... in ascending order, one fused multiply-add each), then a
+ * radix-2 butterfly over the chain index with strides 1, 2, ..., 128. */
+typedef enum { CDF_NORM_LINF = 0, CDF_NORM_L2 = 1 } cdf_norm;
+
+/* Message coding (Sec. 5). MINMAX is the paper's linear quantiser with 2^B - 1 levels;
+ * SYMMETRIC is a zero-centred variant; NONE sends the fp32 row unchanged. */
+typedef enum { CDF_Q_MINMAX = 0, CDF_Q_SYMMETRIC = 1, CDF_Q_NONE = 2 } cdf_qscheme;
+
+/* What the sender does to its cache after a row is sent (Alg. 2: cached <- current). */
+typedef enum { CDF_COMMIT_NONE = 0, CDF_COMMIT_CUR = 1, CDF_COMMIT_DEQ = 2 } cdf_commit;
+
+/* CSR matrix, column indices ascending within a row. */
+typedef struct {
+  int32_t n_rows, n_cols;
+  int64_t nnz;
+  const int64_t* rowptr; /* [n_rows + 1], rowptr[0] = 0, rowptr[n_rows] = nnz */
+  const int32_t* colidx; /* [nnz], each in [0, n_cols) */
+  const float* vals;     /* [nnz] */
+} cdf_csr;
+
+/* Host-side text of the last error raised on the calling thread ("" if none). */
+const char* cdf_last_error(void);
+
+/* Bytes of workspace that cover any call on matrices of at most max_rows rows (of a
+ * feature matrix or of a CSR operand, whichever is larger), max_dim columns and
+ * max_nnz stored entries. Host function, no device work. */
+size_t cdf_workspace_bytes(int64_t max_rows, int32_t max_dim, int64_t max_nnz);
+
+/* Bytes of one packed message row: dim*4 for CDF_Q_NONE, else ceil(dim*bits/8). The
+ * paper's message size B*L + 2T bits (Sec. 5) is this plus the 8 bytes of `meta`. */
+size_t cdf_code_row_bytes(int32_t dim, int bits, cdf_qscheme qs);
+
+/*
+ * Adaptive cache test (Alg. 2, the condition of the mirror loop).
+ *   mask[r] = ( ||cur[r] - cached[r]|| > eps * ||cached[r]|| ), strict, product form, so a
+ *   zero cached row is sent on any non-zero difference and an unchanged row never is.
+ *   idx     = ascending list of the rows with mask 1;  *n_sent = their number.
+ * cur, cached : n_rows x dim, leading dimension ld, type dt (read only here).
+ * mask [n_rows] bytes, idx [n_rows] int32 (entries past *n_sent are not written), n_sent [1].
+ * eps must be finite and >= 0.
+ */
+int cdf_cache_filter(const void* cur, const void* cached, int32_t n_rows, int32_t dim, int64_t ld,
+                     cdf_dtype dt, float eps, cdf_norm norm, uint8_t* mask, int32_t* idx,
+                     int32_t* n_sent, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Message build for the listed rows (Alg. 2 "send the difference"; Sec. 5, first equation)
+ * followed by the cache commit. For k < *n_sent, r = idx[k]:
+ *   m = cur[r] - cached[r]  (delta != 0, the paper)   or   m = cur[r]  (delta == 0)
+ *   MINMAX   : lo = min m, hi = max m, Lv = 2^bits - 1, inv = Lv / (hi - lo) (0 if hi == lo),
+ *              q_j = clamp(floor((m_j - lo) * inv + 0.5), 0, Lv)   [fused multiply-add, fp32]
+ *              meta[k] = (lo, hi)
+ *   SYMMETRIC: a = max |m|, Qm = 2^(bits-1) - 1, inv = Qm / a (0 if a == 0),
+ *              q_j = clamp(floor(m_j * inv + 0.5), -Qm, Qm), two's complement in `bits` bits
+ *              meta[k] = (a / Qm, 0)
+ *   NONE     : the fp32 values of m; meta[k] = (0, 0)
+ *   codes row k = cdf_code_row_bytes() bytes; 8 bits: one code per byte; 4 bits: even element
+ *   in the low nibble, odd element in the high nibble, unused tail nibble zero.
+ *   commit: CUR cached[r] <- cur[r];  DEQ cached[r] <- (delta ? cached[r] : 0) + recovered m;
+ *   NONE leaves the cache.
+ * cached may be NULL only if delta == 0 and commit == CDF_COMMIT_NONE.
+ * max_sent bounds *n_sent (capacity of idx / codes / meta); bits is 8 or 4.
+ */
+int cdf_quantize(const void* cur, void* cached, const int32_t* idx, const int32_t* n_sent,
+                 int32_t max_sent, int32_t dim, int64_t ld, cdf_dtype dt, int bits, cdf_qscheme qs,
+                 cdf_commit commit, int delta, uint8_t* codes, float* meta, void* stream);
+
+/*
+ * Message recovery (Sec. 5, second equation) and the receiver's cache update (Alg. 2,
+ * message loop: cached_total <- cached_total + delta). For k < *n_sent:
+ *   MINMAX   : scale = (hi - lo) / Lv,  m~_j = q_j * scale + lo   [fused, fp32]
+ *   SYMMETRIC: m~_j = q_j * meta[k][0]
+ *   NONE     : m~_j = stored fp32 value
+ *   accumulate != 0: dst[idx[k]][j] += m~_j    else: dst[idx[k]][j] = m~_j
+ * dst : rows of leading dimension ld and type dt (bf16: the fp32 result is rounded to
+ * nearest even). Rows listed twice in idx race; idx from cdf_cache_filter has none.
+ */
+int cdf_dequantize(const uint8_t* codes, const float* meta, const int32_t* idx, const int32_t* n_sent,
+                   int32_t max_sent, int32_t dim, int bits, cdf_qscheme qs, void* dst, int64_t ld,
+                   cdf_dtype dt, int accumulate, void* stream);
+
+/*
+ * Aggregation over the normalised adjacency (Sec. 3.1, the product A^_i H of the forward
+ * equation): Y[n_rows x dim] = A * X[n_cols x dim], fp32 accumulation in storage order of
+ * each row, no atomics, bit-reproducible from run to run. `A` is a HOST pointer to a struct
+ * of device arrays. X and Y must not overlap. Empty rows give zero rows.
+ */
+int cdf_spmm_fwd(const cdf_csr* A, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t dim,
+                 cdf_dtype dt, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The transposed product of back-propagation (Sec. 3.1, gradient w.r.t. the layer input):
+ * dX[(n_loc + n_halo) x dim] = A^T * dY[n_loc x dim], computed as a row-gather over `At`,
+ * the CSR of A^T built once by the caller, so it needs no atomics either.
+ */
+int cdf_spmm_bwd(const cdf_csr* At, const void* dY, int64_t ldy, void* dX, int64_t ldx, int32_t dim,
+                 cdf_dtype dt, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Dense transform (Sec. 3.1: Z = (A^ H) W, H' = sigma(Z), sigma = ReLU or identity) on
+ * the matrix cores. M [n x f_in] type dt, W [f_in x f_out] fp32 row-major,
+ * Z (nullable), H (nullable) [n x f_out] fp32 row-major, contiguous.
+ */
+int cdf_dense_fwd(const void* M, int64_t ldm, cdf_dtype dt, const float* W, int32_t n, int32_t f_in,
+                  int32_t f_out, int relu, float* Z, float* H, void* stream);
+
+/*
+ * Gradients of the dense transform (chain rule of Sec. 3.1 with sigma'(z) = [z > 0]):
+ *   dZ = relu ? dH * [Zs > 0] : dH      (Zs: Z or H of the forward pass - same sign test)
+ *   dW [f_in x f_out] fp32 = M^T dZ     (row blocks reduced in a fixed order: reproducible)
+ *   dM [n x f_in] type dt  = dZ W^T     (skipped when dM is NULL)
+ */
+int cdf_dense_bwd(const void* M, int64_t ldm, cdf_dtype dt, const float* W, const float* Zs,
+                  const float* dH, int32_t n, int32_t f_in, int32_t f_out, int relu, float* dW,
+                  void* dM, int64_t lddm, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Forward step of one layer on one partition (Alg. 1 forward line with Alg. 2 and Sec. 5
+ * applied to the rows that cross the partition boundary):
+ *   1. cache test of halo_fresh (what the halo rows' owners hold now) against cache_sent
+ *      (what they last sent)                                   -> mask, idx, n_sent
+ *   2. message build + commit of cache_sent                    -> codes, meta
+ *   3. recovery and update of the halo rows of xfull (+= when delta, = otherwise)
+ *   4. M = A * xfull                 5. Z = M W, H = sigma(Z)
+ * `A` is a host pointer; all other pointers are device pointers.
+ */
+typedef struct {
+  const cdf_csr* A;       /* host pointer; n_rows = n_loc, n_cols = n_loc + n_halo */
+  int32_t n_loc, n_halo, f_in, f_out;
+  cdf_dtype dt;           /* type of xfull, halo_fresh, cache_sent, M */
+  int relu;
+  void* xfull;            /* (n_loc+n_halo) x f_in, ld = f_in; halo rows updated in place */
+  const void* halo_fresh; /* n_halo x f_in */
+  void* cache_sent;       /* n_halo x f_in, updated in place by the commit */
+  const float* W;         /* f_in x f_out */
+  float eps;
+  cdf_norm norm;
+  int bits;
+  cdf_qscheme qs;
+  cdf_commit commit;
+  int delta;              /* 1: difference messages, receiver adds (the paper); 0: value messages */
+  void* M;                /* out: n_loc x f_in, type dt (kept for the backward step) */
+  float* Z;               /* out, nullable: n_loc x f_out */
+  float* H;               /* out: n_loc x f_out */
+  uint8_t* mask;          /* out: [n_halo] */
+  int32_t* idx;           /* out: [n_halo] */
+  int32_t* n_sent;        /* out: [1] */
+  uint8_t* codes;         /* out: [n_halo * cdf_code_row_bytes(f_in, bits, qs)] */
+  float* meta;            /* out: [n_halo * 2] */
+} cdf_layer_fwd_args;
+
+int cdf_gcn_layer_fwd(const cdf_layer_fwd_args* args /* host */, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward step of one layer on one partition (Alg. 1 backward lines; the cache and the
+ * quantiser applied to gradients exactly as to features, Sec. 4.1):
+ *   1. dZ = dH * sigma'(Zs);  dW = M^T dZ;  dM = dZ W^T
+ *   2. dxfull = A^T dM : rows [0, n_loc) local input gradients, rows [n_loc, n_loc+n_halo)
+ *      partial gradients owed to the owners of the halo rows
+ *   3. cache test of those halo gradient rows against gcache_sent -> mask, idx, n_sent
+ *   4. message build + commit of gcache_sent                     -> codes, meta
+ * Steps 2-4 are skipped when need_dx == 0 (first layer: inputs need no gradient).
+ */
+typedef struct {
+  const cdf_csr* At;      /* host pointer; n_rows = n_loc + n_halo, n_cols = n_loc */
+  int32_t n_loc, n_halo, f_in, f_out;
+  cdf_dtype dt;           /* type of M, dM, dxfull, gcache_sent */
+  int relu, need_dx;
+  const float* dH;        /* n_loc x f_out */
+  const float* Zs;        /* n_loc x f_out: Z or H of the forward step (unused if !relu) */
+  const void* M;          /* n_loc x f_in */
+  const float* W;         /* f_in x f_out */
+  float* dW;              /* out: f_in x f_out */
+  void* dM;               /* out / scratch: n_loc x f_in, type dt */
+  void* dxfull;           /* out: (n_loc+n_halo) x f_in, type dt */
+  void* gcache_sent;      /* n_halo x f_in, updated in place by the commit */
+  float eps;
+  cdf_norm norm;
+  int bits;
+  cdf_qscheme qs;
+  cdf_commit commit;
+  int delta;
+  uint8_t* mask;
+  int32_t* idx;
+  int32_t* n_sent;
+  uint8_t* codes;
+  float* meta;
+} cdf_layer_bwd_args;
+
+int cdf_gcn_layer_bwd(const cdf_layer_bwd_args* args /* host */, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CDF_H */

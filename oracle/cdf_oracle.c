@@ -210,8 +210,8 @@ int orc_quantize(const void* cur, void* cached, const int32_t* idx, int32_t n_se
         float inv = range > 0.0f ? (float)Lv / range : 0.0f;
         for (int j = 0; j < dim; ++j) {
           float t = floorf(fmaf(m[j] - lo, inv, 0.5f));
-          int v = (int)t;
-          q[j] = v < 0 ? 0 : (v > Lv ? Lv : v);
+          t = fminf(fmaxf(t, 0.0f), (float)Lv); /* clamp before the integer conversion */
+          q[j] = (int)t;
         }
         m0 = lo;
         m1 = hi;
@@ -223,8 +223,8 @@ int orc_quantize(const void* cur, void* cached, const int32_t* idx, int32_t n_se
         float inv = a > 0.0f ? (float)Qm / a : 0.0f;
         for (int j = 0; j < dim; ++j) {
           float t = floorf(fmaf(m[j], inv, 0.5f));
-          int v = (int)t;
-          q[j] = v < -Qm ? -Qm : (v > Qm ? Qm : v);
+          t = fminf(fmaxf(t, (float)-Qm), (float)Qm);
+          q[j] = (int)t;
         }
         scale = a / (float)Qm;
         m0 = scale;

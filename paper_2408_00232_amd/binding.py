@@ -1,0 +1,190 @@
+"""Thin ctypes binding of libcdf.so: argument marshalling only.
+
+Functions carry the names of the C entry points (include/cdf.h). Tensors are
+torch CUDA tensors used as device memory; every step runs in the library's
+kernels on the current torch stream. There is no fallback: if the library is
+missing or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libcdf.so")
+
+F32, BF16 = 0, 1
+NORM_LINF, NORM_L2 = 0, 1
+Q_MINMAX, Q_SYMMETRIC, Q_NONE = 0, 1, 2
+COMMIT_NONE, COMMIT_CUR, COMMIT_DEQ = 0, 1, 2
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
+
+EXPORTS = ["cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_quantize",
+           "cdf_dequantize", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
+           "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd"]
+
+
+class CdfError(RuntimeError):
+    def __init__(self, fn, code, text):
+        super().__init__(f"{fn} failed with status {code}: {text}")
+        self.code = code
+
+
+class cdf_csr(ctypes.Structure):
+    _fields_ = [("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
+                ("rowptr", ctypes.c_void_p), ("colidx", ctypes.c_void_p), ("vals", ctypes.c_void_p)]
+
+
+class cdf_layer_fwd_args(ctypes.Structure):
+    _fields_ = [("A", ctypes.POINTER(cdf_csr)),
+                ("n_loc", ctypes.c_int32), ("n_halo", ctypes.c_int32), ("f_in", ctypes.c_int32),
+                ("f_out", ctypes.c_int32), ("dt", ctypes.c_int), ("relu", ctypes.c_int),
+                ("xfull", ctypes.c_void_p), ("halo_fresh", ctypes.c_void_p), ("cache_sent", ctypes.c_void_p),
+                ("W", ctypes.c_void_p), ("eps", ctypes.c_float), ("norm", ctypes.c_int), ("bits", ctypes.c_int),
+                ("qs", ctypes.c_int), ("commit", ctypes.c_int), ("delta", ctypes.c_int),
+                ("M", ctypes.c_void_p), ("Z", ctypes.c_void_p), ("H", ctypes.c_void_p),
+                ("mask", ctypes.c_void_p), ("idx", ctypes.c_void_p), ("n_sent", ctypes.c_void_p),
+                ("codes", ctypes.c_void_p), ("meta", ctypes.c_void_p)]
+
+
+class cdf_layer_bwd_args(ctypes.Structure):
+    _fields_ = [("At", ctypes.POINTER(cdf_csr)),
+                ("n_loc", ctypes.c_int32), ("n_halo", ctypes.c_int32), ("f_in", ctypes.c_int32),
+                ("f_out", ctypes.c_int32), ("dt", ctypes.c_int), ("relu", ctypes.c_int), ("need_dx", ctypes.c_int),
+                ("dH", ctypes.c_void_p), ("Zs", ctypes.c_void_p), ("M", ctypes.c_void_p), ("W", ctypes.c_void_p),
+                ("dW", ctypes.c_void_p), ("dM", ctypes.c_void_p), ("dxfull", ctypes.c_void_p),
+                ("gcache_sent", ctypes.c_void_p), ("eps", ctypes.c_float), ("norm", ctypes.c_int),
+                ("bits", ctypes.c_int), ("qs", ctypes.c_int), ("commit", ctypes.c_int), ("delta", ctypes.c_int),
+                ("mask", ctypes.c_void_p), ("idx", ctypes.c_void_p), ("n_sent", ctypes.c_void_p),
+                ("codes", ctypes.c_void_p), ("meta", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def load():
+    """Load libcdf.so (built in-tree). Raises if it is absent: there is no other path."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2408_00232_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        lib.cdf_last_error.restype = ctypes.c_char_p
+        lib.cdf_workspace_bytes.restype = ctypes.c_size_t
+        lib.cdf_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int64]
+        lib.cdf_code_row_bytes.restype = ctypes.c_size_t
+        lib.cdf_code_row_bytes.argtypes = [ctypes.c_int32, ctypes.c_int, ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def _check(fn, rc):
+    if rc != 0:
+        raise CdfError(fn, rc, load().cdf_last_error().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return ctypes.c_void_p(None)
+    assert t.is_cuda, "device tensors only"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def dtype_of(t) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _ld(t) -> int:
+    assert t.dim() == 2 and t.stride(1) == 1
+    return t.stride(0)
+
+
+def make_csr(n_rows, n_cols, rowptr, colidx, vals) -> cdf_csr:
+    """Host struct of device arrays (the tensors must outlive its use)."""
+    assert rowptr.dtype == torch.int64 and colidx.dtype == torch.int32 and vals.dtype == torch.float32
+    assert rowptr.numel() == n_rows + 1
+    return cdf_csr(n_rows, n_cols, colidx.numel(), rowptr.data_ptr(), colidx.data_ptr(), vals.data_ptr())
+
+
+def cdf_workspace_bytes(max_rows: int, max_dim: int, max_nnz: int) -> int:
+    return int(load().cdf_workspace_bytes(max_rows, max_dim, max_nnz))
+
+
+def cdf_code_row_bytes(dim: int, bits: int, qs: int) -> int:
+    return int(load().cdf_code_row_bytes(dim, bits, qs))
+
+
+def cdf_cache_filter(cur, cached, eps, norm, mask, idx, n_sent, ws):
+    rc = load().cdf_cache_filter(_ptr(cur), _ptr(cached), ctypes.c_int32(cur.shape[0]), ctypes.c_int32(cur.shape[1]),
+                                 ctypes.c_int64(_ld(cur)), ctypes.c_int(dtype_of(cur)), ctypes.c_float(eps),
+                                 ctypes.c_int(norm), _ptr(mask), _ptr(idx), _ptr(n_sent), _ptr(ws),
+                                 ctypes.c_size_t(ws.numel() * ws.element_size()), _stream())
+    _check("cdf_cache_filter", rc)
+
+
+def cdf_quantize(cur, cached, idx, n_sent, max_sent, bits, qs, commit, delta, codes, meta):
+    rc = load().cdf_quantize(_ptr(cur), _ptr(cached), _ptr(idx), _ptr(n_sent), ctypes.c_int32(max_sent),
+                             ctypes.c_int32(cur.shape[1]), ctypes.c_int64(_ld(cur)), ctypes.c_int(dtype_of(cur)),
+                             ctypes.c_int(bits), ctypes.c_int(qs), ctypes.c_int(commit), ctypes.c_int(1 if delta else 0),
+                             _ptr(codes), _ptr(meta), _stream())
+    _check("cdf_quantize", rc)
+
+
+def cdf_dequantize(codes, meta, idx, n_sent, max_sent, bits, qs, dst, accumulate):
+    rc = load().cdf_dequantize(_ptr(codes), _ptr(meta), _ptr(idx), _ptr(n_sent), ctypes.c_int32(max_sent),
+                               ctypes.c_int32(dst.shape[1]), ctypes.c_int(bits), ctypes.c_int(qs), _ptr(dst),
+                               ctypes.c_int64(_ld(dst)), ctypes.c_int(dtype_of(dst)),
+                               ctypes.c_int(1 if accumulate else 0), _stream())
+    _check("cdf_dequantize", rc)
+
+
+def _spmm(name, A: cdf_csr, X, Y, ws):
+    fn = getattr(load(), name)
+    rc = fn(ctypes.byref(A), _ptr(X), ctypes.c_int64(_ld(X)), _ptr(Y), ctypes.c_int64(_ld(Y)),
+            ctypes.c_int32(X.shape[1]), ctypes.c_int(dtype_of(X)), _ptr(ws),
+            ctypes.c_size_t(ws.numel() * ws.element_size()), _stream())
+    _check(name, rc)
+
+
+def cdf_spmm_fwd(A: cdf_csr, X, Y, ws):
+    _spmm("cdf_spmm_fwd", A, X, Y, ws)
+
+
+def cdf_spmm_bwd(At: cdf_csr, dY, dX, ws):
+    _spmm("cdf_spmm_bwd", At, dY, dX, ws)
+
+
+def cdf_dense_fwd(M, W, relu, Z, H):
+    rc = load().cdf_dense_fwd(_ptr(M), ctypes.c_int64(_ld(M)), ctypes.c_int(dtype_of(M)), _ptr(W),
+                              ctypes.c_int32(M.shape[0]), ctypes.c_int32(W.shape[0]), ctypes.c_int32(W.shape[1]),
+                              ctypes.c_int(1 if relu else 0), _ptr(Z), _ptr(H), _stream())
+    _check("cdf_dense_fwd", rc)
+
+
+def cdf_dense_bwd(M, W, Zs, dH, relu, dW, dM, ws):
+    rc = load().cdf_dense_bwd(_ptr(M), ctypes.c_int64(_ld(M)), ctypes.c_int(dtype_of(M)), _ptr(W), _ptr(Zs), _ptr(dH),
+                              ctypes.c_int32(M.shape[0]), ctypes.c_int32(W.shape[0]), ctypes.c_int32(W.shape[1]),
+                              ctypes.c_int(1 if relu else 0), _ptr(dW), _ptr(dM),
+                              ctypes.c_int64(_ld(dM) if dM is not None else W.shape[0]), _ptr(ws),
+                              ctypes.c_size_t(ws.numel() * ws.element_size()), _stream())
+    _check("cdf_dense_bwd", rc)
+
+
+def cdf_gcn_layer_fwd(args: cdf_layer_fwd_args, ws):
+    rc = load().cdf_gcn_layer_fwd(ctypes.byref(args), _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()),
+                                  _stream())
+    _check("cdf_gcn_layer_fwd", rc)
+
+
+def cdf_gcn_layer_bwd(args: cdf_layer_bwd_args, ws):
+    rc = load().cdf_gcn_layer_bwd(ctypes.byref(args), _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()),
+                                  _stream())
+    _check("cdf_gcn_layer_bwd", rc)

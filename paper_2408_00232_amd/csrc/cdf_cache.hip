@@ -1,0 +1,265 @@
+// Adaptive cache test (Alg. 2, condition of the mirror loop) and the ordered
+// compaction of the rows that fail it.
+//
+// Three launches, no atomics:
+//   1. filter_kernel  - streams cur and cached once, writes mask[r] and one count per
+//                       block of kRowsPerBlock rows                     (HBM bound)
+//   2. scan_kernel    - one block: exclusive scan of the block counts, total -> n_sent
+//   3. compact_kernel - block b ranks its mask bytes and writes idx ascending
+//
+// Lane mapping. A row is read as vectors of EPV elements (16 bytes for fp32 when
+// alignment allows). Rows with at most 64 vectors are handled by groups of
+// G = 2^glog lanes, 64/G rows per wavefront at a time; longer rows take the whole
+// wavefront and loop. For the L2 norm the fp32 summation order is fixed (256
+// interleaved chains, then a radix-2 butterfly over the chain index): element j of a
+// row sits in chain j mod 256, and with this mapping chain = c + EPV*lane + 64*EPV*a,
+// where c is the component inside the vector and a = iteration mod (4/EPV) selects
+// one of 4/EPV accumulators per lane-component. The butterfly then runs over c, the
+// lane bits and a, in that order.
+#include "cdf_common.h"
+
+namespace cdf {
+
+constexpr int kRowsPerBlock = 256;  // rows per block in all three kernels
+constexpr int kFilterThreads = 256;
+
+template <typename T, int EPV, int NORM>
+__global__ __launch_bounds__(kFilterThreads) void filter_kernel(
+    const T* __restrict__ cur, const T* __restrict__ cached, int n_rows, int dim, int64_t ld, float eps,
+    int glog, uint8_t* __restrict__ mask, int* __restrict__ block_counts) {
+  constexpr int NACC = 4 / EPV;  // accumulators per lane-component (L2 chains)
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int G = 1 << glog;
+  const int lg = lane & (G - 1);
+  const int sub = lane >> glog;       // which row of the step this lane works on
+  const int rows_per_step = 64 >> glog;
+  const int nvec = dim / EPV;
+  const int row0 = blockIdx.x * kRowsPerBlock + wave * 64;
+  int sent_here = 0;
+
+  for (int s = 0; s < 64; s += rows_per_step) {
+    const int row = row0 + s + sub;
+    const bool live = row < n_rows;
+    float accd[NACC][EPV], accc[NACC][EPV];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a)
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) accd[a][c] = accc[a][c] = 0.0f;
+    if (live) {
+      const T* pc = cur + static_cast<int64_t>(row) * ld;
+      const T* pz = cached + static_cast<int64_t>(row) * ld;
+      for (int v0 = lg; v0 < nvec; v0 += G * NACC) {
+#pragma unroll
+        for (int a = 0; a < NACC; ++a) {
+          const int v = v0 + a * G;
+          if (v < nvec) {
+            float x[EPV], z[EPV];
+            VecIO<T, EPV>::load(pc + static_cast<int64_t>(v) * EPV, x);
+            VecIO<T, EPV>::load(pz + static_cast<int64_t>(v) * EPV, z);
+#pragma unroll
+            for (int c = 0; c < EPV; ++c) {
+              const float d = x[c] - z[c];
+              if (NORM == CDF_NORM_LINF) {
+                accd[a][c] = fmaxf(accd[a][c], fabsf(d));
+                accc[a][c] = fmaxf(accc[a][c], fabsf(z[c]));
+              } else {
+                accd[a][c] = __fmaf_rn(d, d, accd[a][c]);
+                accc[a][c] = __fmaf_rn(z[c], z[c], accc[a][c]);
+              }
+            }
+          }
+        }
+      }
+    }
+    // butterfly: components, lanes, accumulators (ascending chain-index bits)
+    float D[NACC], C[NACC];
+#pragma unroll
+    for (int a = 0; a < NACC; ++a) {
+      float d, c;
+      if (NORM == CDF_NORM_LINF) {
+        d = accd[a][0];
+        c = accc[a][0];
+#pragma unroll
+        for (int k = 1; k < EPV; ++k) {
+          d = fmaxf(d, accd[a][k]);
+          c = fmaxf(c, accc[a][k]);
+        }
+        d = group_max(d, G);
+        c = group_max(c, G);
+      } else {
+        if (EPV == 4) {
+          d = (accd[a][0] + accd[a][1]) + (accd[a][2 % EPV] + accd[a][3 % EPV]);
+          c = (accc[a][0] + accc[a][1]) + (accc[a][2 % EPV] + accc[a][3 % EPV]);
+        } else if (EPV == 2) {
+          d = accd[a][0] + accd[a][1 % EPV];
+          c = accc[a][0] + accc[a][1 % EPV];
+        } else {
+          d = accd[a][0];
+          c = accc[a][0];
+        }
+        d = group_sum(d, G);
+        c = group_sum(c, G);
+      }
+      D[a] = d;
+      C[a] = c;
+    }
+    float Dr, Cr;
+    if (NORM == CDF_NORM_LINF) {
+      Dr = D[0];
+      Cr = C[0];
+#pragma unroll
+      for (int a = 1; a < NACC; ++a) {
+        Dr = fmaxf(Dr, D[a]);
+        Cr = fmaxf(Cr, C[a]);
+      }
+    } else if (NACC == 4) {
+      Dr = (D[0] + D[1 % NACC]) + (D[2 % NACC] + D[3 % NACC]);
+      Cr = (C[0] + C[1 % NACC]) + (C[2 % NACC] + C[3 % NACC]);
+    } else if (NACC == 2) {
+      Dr = D[0] + D[1 % NACC];
+      Cr = C[0] + C[1 % NACC];
+    } else {
+      Dr = D[0];
+      Cr = C[0];
+    }
+    bool send;
+    if (NORM == CDF_NORM_LINF) {
+      const float thr = eps * Cr;
+      send = Dr > thr;
+    } else {
+      const float e2 = eps * eps;
+      const float thr = e2 * Cr;
+      send = Dr > thr;
+    }
+    const bool head = live && lg == 0;
+    if (head) mask[row] = send ? 1 : 0;
+    sent_here += __popcll(__ballot(head && send));
+  }
+
+  __shared__ int wave_cnt[kFilterThreads / 64];
+  if (lane == 0) wave_cnt[wave] = sent_here;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int t = 0;
+    for (int w = 0; w < kFilterThreads / 64; ++w) t += wave_cnt[w];
+    block_counts[blockIdx.x] = t;
+  }
+}
+
+// Exclusive scan of n counts by one block; offsets[i] = sum of counts[0..i), *total = sum.
+__global__ __launch_bounds__(1024) void scan_kernel(const int* __restrict__ counts, int n,
+                                                    int* __restrict__ offsets, int* __restrict__ total) {
+  __shared__ int wsum[16];
+  __shared__ int carry;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (threadIdx.x == 0) carry = 0;
+  __syncthreads();
+  for (int base = 0; base < n; base += 1024) {
+    const int i = base + threadIdx.x;
+    const int v = i < n ? counts[i] : 0;
+    int incl = v;
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(incl, off, kWave);
+      if (lane >= off) incl += t;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int wbase = 0;
+    for (int w = 0; w < wave; ++w) wbase += wsum[w];
+    const int c = carry;
+    if (i < n) offsets[i] = c + wbase + incl - v;
+    __syncthreads();
+    if (threadIdx.x == 1023) carry = c + wbase + incl;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) *total = carry;
+}
+
+__global__ __launch_bounds__(kRowsPerBlock) void compact_kernel(const uint8_t* __restrict__ mask, int n_rows,
+                                                                const int* __restrict__ offsets,
+                                                                int* __restrict__ idx) {
+  __shared__ int wcnt[kRowsPerBlock / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * kRowsPerBlock + threadIdx.x;
+  const bool on = row < n_rows && mask[row] != 0;
+  const unsigned long long b = __ballot(on);
+  if (lane == 0) wcnt[wave] = __popcll(b);
+  __syncthreads();
+  int base = offsets[blockIdx.x];
+  for (int w = 0; w < wave; ++w) base += wcnt[w];
+  if (on) idx[base + __popcll(b & ((1ull << lane) - 1ull))] = row;
+}
+
+template <typename T, int EPV>
+static void launch_filter(const void* cur, const void* cached, int n_rows, int dim, int64_t ld, float eps,
+                          cdf_norm norm, int glog, uint8_t* mask, int* counts, int nblocks, hipStream_t st) {
+  const T* a = static_cast<const T*>(cur);
+  const T* b = static_cast<const T*>(cached);
+  if (norm == CDF_NORM_LINF)
+    filter_kernel<T, EPV, CDF_NORM_LINF><<<nblocks, kFilterThreads, 0, st>>>(a, b, n_rows, dim, ld, eps, glog,
+                                                                             mask, counts);
+  else
+    filter_kernel<T, EPV, CDF_NORM_L2><<<nblocks, kFilterThreads, 0, st>>>(a, b, n_rows, dim, ld, eps, glog,
+                                                                           mask, counts);
+}
+
+size_t filter_workspace_bytes(int64_t n_rows) {
+  return align_up(static_cast<size_t>(2 * (ceil_div(n_rows, kRowsPerBlock) + 1)) * sizeof(int), 256);
+}
+
+}  // namespace cdf
+
+using namespace cdf;
+
+extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_rows, int32_t dim, int64_t ld,
+                                cdf_dtype dt, float eps, cdf_norm norm, uint8_t* mask, int32_t* idx,
+                                int32_t* n_sent, void* ws, size_t ws_bytes, void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  CDF_REQUIRE(n_rows >= 0 && dim > 0 && ld >= dim, "cdf_cache_filter: bad shape n_rows=%d dim=%d ld=%lld",
+              n_rows, dim, (long long)ld);
+  CDF_REQUIRE(n_sent != nullptr, "cdf_cache_filter: n_sent is null");
+  CDF_REQUIRE(eps >= 0.0f && eps <= 3.0e38f, "cdf_cache_filter: eps must be finite and >= 0");
+  if (dt != CDF_F32 && dt != CDF_BF16) CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_cache_filter: dtype %d", (int)dt);
+  if (norm != CDF_NORM_LINF && norm != CDF_NORM_L2)
+    CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_cache_filter: norm %d", (int)norm);
+  if (n_rows == 0) {
+    // nothing to test: the count is still defined (written by a kernel, not a memset node,
+    // so that the call can be captured into a graph)
+    scan_kernel<<<1, 1024, 0, st>>>(nullptr, 0, nullptr, n_sent);
+    CDF_LAUNCH_CHECK("cdf_cache_filter/scan");
+    return CDF_OK;
+  }
+  CDF_REQUIRE(cur && cached && mask && idx, "cdf_cache_filter: null pointer");
+  const size_t esz = elem_bytes(dt);
+  CDF_REQUIRE(aligned(cur, esz) && aligned(cached, esz) && aligned(idx, 4) && aligned(n_sent, 4),
+              "cdf_cache_filter: misaligned pointer");
+  const int nblocks = static_cast<int>(ceil_div(n_rows, kRowsPerBlock));
+  if (!ws || ws_bytes < filter_workspace_bytes(n_rows) || !aligned(ws, 4))
+    CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_cache_filter: workspace too small (%zu < %zu)", ws_bytes,
+             filter_workspace_bytes(n_rows));
+  int* counts = static_cast<int*>(ws);
+  int* offsets = counts + nblocks + 1;
+
+  const int epv = pick_epv(dim, ld, esz, cur, cached);
+  const int nvec = dim / epv;
+  const int glog = nvec >= 64 ? 6 : log2_ceil(nvec);
+#define CDF_FILTER_CASE(T, E)                                                                       \
+  launch_filter<T, E>(cur, cached, n_rows, dim, ld, eps, norm, glog, mask, counts, nblocks, st)
+  if (dt == CDF_F32) {
+    if (epv == 4) CDF_FILTER_CASE(float, 4);
+    else if (epv == 2) CDF_FILTER_CASE(float, 2);
+    else CDF_FILTER_CASE(float, 1);
+  } else {
+    if (epv == 4) CDF_FILTER_CASE(bf16_t, 4);
+    else if (epv == 2) CDF_FILTER_CASE(bf16_t, 2);
+    else CDF_FILTER_CASE(bf16_t, 1);
+  }
+#undef CDF_FILTER_CASE
+  CDF_LAUNCH_CHECK("cdf_cache_filter/filter");
+  scan_kernel<<<1, 1024, 0, st>>>(counts, nblocks, offsets, n_sent);
+  CDF_LAUNCH_CHECK("cdf_cache_filter/scan");
+  compact_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(mask, n_rows, offsets, idx);
+  CDF_LAUNCH_CHECK("cdf_cache_filter/compact");
+  return CDF_OK;
+}

@@ -1,0 +1,105 @@
+// The per-partition layer step (Alg. 1 with Alg. 2 and Sec. 5 on the rows that cross the
+// partition boundary): host-side sequencing of the kernels on one stream, workspace
+// partitioning, and the error text.
+#include <stdarg.h>
+
+#include "cdf_common.h"
+
+namespace cdf {
+
+size_t filter_workspace_bytes(int64_t n_rows);
+size_t spmm_workspace_bytes(int64_t nnz, int32_t dim);
+size_t dense_workspace_bytes(int64_t n, int32_t f, int32_t g);
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+}
+
+static size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
+
+}  // namespace cdf
+
+using namespace cdf;
+
+extern "C" const char* cdf_last_error(void) { return g_err; }
+
+extern "C" size_t cdf_workspace_bytes(int64_t max_rows, int32_t max_dim, int64_t max_nnz) {
+  if (max_rows < 0 || max_dim <= 0 || max_nnz < 0) return 0;
+  return filter_workspace_bytes(max_rows) +
+         max_sz(spmm_workspace_bytes(max_nnz, max_dim), dense_workspace_bytes(max_rows, max_dim, max_dim));
+}
+
+extern "C" int cdf_gcn_layer_fwd(const cdf_layer_fwd_args* p, void* ws, size_t ws_bytes, void* stream) {
+  CDF_REQUIRE(p != nullptr && p->A != nullptr, "cdf_gcn_layer_fwd: null argument block");
+  CDF_REQUIRE(p->n_loc >= 0 && p->n_halo >= 0 && p->f_in > 0 && p->f_out > 0, "cdf_gcn_layer_fwd: bad sizes");
+  CDF_REQUIRE(p->A->n_rows == p->n_loc && p->A->n_cols == p->n_loc + p->n_halo,
+              "cdf_gcn_layer_fwd: adjacency is %d x %d, expected %d x %d", p->A->n_rows, p->A->n_cols, p->n_loc,
+              p->n_loc + p->n_halo);
+  CDF_REQUIRE(p->xfull && p->W && p->M && p->H, "cdf_gcn_layer_fwd: null matrix");
+  if (p->dt != CDF_F32 && p->dt != CDF_BF16) CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_gcn_layer_fwd: dtype %d", (int)p->dt);
+  const size_t fw = filter_workspace_bytes(p->n_halo);
+  const size_t need = fw + spmm_workspace_bytes(p->A->nnz, p->f_in);
+  if (!ws || !aligned(ws, 256) || ws_bytes < need)
+    CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_gcn_layer_fwd: workspace too small or unaligned (%zu < %zu)", ws_bytes, need);
+  char* w = static_cast<char*>(ws);
+  const size_t esz = elem_bytes(p->dt);
+  int rc;
+  if (p->n_halo > 0) {
+    CDF_REQUIRE(p->halo_fresh && p->cache_sent && p->mask && p->idx && p->n_sent && p->codes && p->meta,
+                "cdf_gcn_layer_fwd: null halo buffer");
+    rc = cdf_cache_filter(p->halo_fresh, p->cache_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->eps, p->norm, p->mask,
+                          p->idx, p->n_sent, w, fw, stream);
+    if (rc != CDF_OK) return rc;
+    rc = cdf_quantize(p->halo_fresh, p->cache_sent, p->idx, p->n_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->bits,
+                      p->qs, p->commit, p->delta, p->codes, p->meta, stream);
+    if (rc != CDF_OK) return rc;
+    void* halo_rows = static_cast<char*>(p->xfull) + static_cast<size_t>(p->n_loc) * p->f_in * esz;
+    rc = cdf_dequantize(p->codes, p->meta, p->idx, p->n_sent, p->n_halo, p->f_in, p->bits, p->qs, halo_rows, p->f_in,
+                        p->dt, p->delta ? 1 : 0, stream);
+    if (rc != CDF_OK) return rc;
+  }
+  rc = cdf_spmm_fwd(p->A, p->xfull, p->f_in, p->M, p->f_in, p->f_in, p->dt, w + fw, ws_bytes - fw, stream);
+  if (rc != CDF_OK) return rc;
+  return cdf_dense_fwd(p->M, p->f_in, p->dt, p->W, p->n_loc, p->f_in, p->f_out, p->relu, p->Z, p->H, stream);
+}
+
+extern "C" int cdf_gcn_layer_bwd(const cdf_layer_bwd_args* p, void* ws, size_t ws_bytes, void* stream) {
+  CDF_REQUIRE(p != nullptr, "cdf_gcn_layer_bwd: null argument block");
+  CDF_REQUIRE(p->n_loc >= 0 && p->n_halo >= 0 && p->f_in > 0 && p->f_out > 0, "cdf_gcn_layer_bwd: bad sizes");
+  CDF_REQUIRE(p->dH && p->M && p->W && p->dW && (!p->relu || p->Zs), "cdf_gcn_layer_bwd: null matrix");
+  if (p->dt != CDF_F32 && p->dt != CDF_BF16) CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_gcn_layer_bwd: dtype %d", (int)p->dt);
+  if (p->need_dx) {
+    CDF_REQUIRE(p->At != nullptr && p->dM && p->dxfull, "cdf_gcn_layer_bwd: need_dx without At / dM / dxfull");
+    CDF_REQUIRE(p->At->n_rows == p->n_loc + p->n_halo && p->At->n_cols == p->n_loc,
+                "cdf_gcn_layer_bwd: transposed adjacency is %d x %d, expected %d x %d", p->At->n_rows, p->At->n_cols,
+                p->n_loc + p->n_halo, p->n_loc);
+  }
+  const size_t fw = filter_workspace_bytes(p->n_halo);
+  size_t need = fw + dense_workspace_bytes(p->n_loc, p->f_in, p->f_out);
+  if (p->need_dx) need = max_sz(need, fw + spmm_workspace_bytes(p->At->nnz, p->f_in));
+  if (!ws || !aligned(ws, 256) || ws_bytes < need)
+    CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_gcn_layer_bwd: workspace too small or unaligned (%zu < %zu)", ws_bytes, need);
+  char* w = static_cast<char*>(ws);
+  const size_t esz = elem_bytes(p->dt);
+  int rc = cdf_dense_bwd(p->M, p->f_in, p->dt, p->W, p->Zs, p->dH, p->n_loc, p->f_in, p->f_out, p->relu, p->dW,
+                         p->need_dx ? p->dM : nullptr, p->f_in, w + fw, ws_bytes - fw, stream);
+  if (rc != CDF_OK || !p->need_dx) return rc;
+  rc = cdf_spmm_bwd(p->At, p->dM, p->f_in, p->dxfull, p->f_in, p->f_in, p->dt, w + fw, ws_bytes - fw, stream);
+  if (rc != CDF_OK) return rc;
+  if (p->n_halo > 0) {
+    CDF_REQUIRE(p->gcache_sent && p->mask && p->idx && p->n_sent && p->codes && p->meta,
+                "cdf_gcn_layer_bwd: null halo buffer");
+    const void* halo_rows = static_cast<const char*>(p->dxfull) + static_cast<size_t>(p->n_loc) * p->f_in * esz;
+    rc = cdf_cache_filter(halo_rows, p->gcache_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->eps, p->norm, p->mask,
+                          p->idx, p->n_sent, w, fw, stream);
+    if (rc != CDF_OK) return rc;
+    rc = cdf_quantize(halo_rows, p->gcache_sent, p->idx, p->n_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->bits,
+                      p->qs, p->commit, p->delta, p->codes, p->meta, stream);
+  }
+  return rc;
+}

@@ -1,0 +1,307 @@
+// CSR aggregation Y = A X over the normalised adjacency (Sec. 3.1) and its transposed
+// counterpart for back-propagation (the same kernel on the CSR of A^T).
+//
+// Work split: the stored entries are cut into chunks of kChunk consecutive entries and
+// each wavefront takes one chunk, whatever rows it covers - a power-law degree
+// distribution (rows of 1 to several 10^5 entries) therefore loads every wavefront
+// equally. Inside a chunk the wavefront walks the entries in storage order: the 64
+// lanes first fetch 64 (column, value) pairs with one coalesced load each, then every
+// entry's feature row is gathered by the whole wavefront (lane l reads elements
+// [l*EPV, l*EPV+EPV) of each 64*EPV-wide pass, a contiguous 16-byte-per-lane read),
+// several gathers in flight at a time, and accumulated in fp32 registers. Column ids
+// and values reach all lanes through v_readlane (scalar broadcast), not LDS. Row ends
+// are wave-uniform: at a row end the accumulator is stored as one coalesced row of Y.
+//
+// Rows that straddle chunk borders: the piece at the start of a chunk that continues an
+// earlier row goes to phead[chunk], the piece at the end of a chunk that continues into
+// the next goes to ptail[chunk] (both fp32); a second kernel adds a row's pieces in
+// chunk order and writes the row once. No atomics: results are bit-reproducible.
+#include "cdf_common.h"
+
+namespace cdf {
+
+constexpr int kChunk = 256;        // stored entries per wavefront
+constexpr int kSpmmThreads = 256;  // 4 wavefronts per block
+constexpr int kSpmmWaves = kSpmmThreads / 64;
+
+// chunk_row[c] = row that holds stored entry c*kChunk (c >= 1; entry 0 is handled as row 0).
+__global__ void chunk_rows_kernel(const int64_t* __restrict__ rowptr, int n_rows, int* __restrict__ chunk_row) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_rows) return;
+  const int64_t a = rowptr[r], b = rowptr[r + 1];
+  for (int64_t c = (a + kChunk - 1) / kChunk; c * kChunk < b; ++c) chunk_row[c] = r;
+}
+
+template <typename T, int EPV, int NP>
+__global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
+    const int64_t* __restrict__ rowptr, const int* __restrict__ colidx, const float* __restrict__ vals,
+    int n_rows, int64_t nnz, const T* __restrict__ X, int64_t ldx, T* __restrict__ Y, int64_t ldy, int dim,
+    const int* __restrict__ chunk_row, int64_t nchunks, float* __restrict__ phead, float* __restrict__ ptail,
+    int* __restrict__ tail_row) {
+  constexpr int U = (8 / NP) > 0 ? (8 / NP) : 1;  // feature rows in flight per wavefront
+  const int lane = threadIdx.x & 63;
+  const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + (threadIdx.x >> 6);
+  if (chunk >= nchunks) return;
+  const int64_t s = chunk * kChunk;
+  const int L = static_cast<int>(nnz - s < kChunk ? nnz - s : kChunk);
+
+  int r = chunk == 0 ? 0 : chunk_row[chunk];
+  bool head = chunk > 0 && rowptr[r] < s;
+
+  // window of 64 row ends, relative to s and clipped, one per lane
+  auto load_rel = [&](int rbase) -> int {
+    const int rr = rbase + lane;
+    if (rr < n_rows) {
+      const int64_t d = rowptr[rr + 1] - s;
+      return d > kChunk ? kChunk + 1 : static_cast<int>(d);
+    }
+    return kChunk + 2;  // past the last row: matches nothing
+  };
+  int r_base = r;
+  int rel = load_rel(r_base);
+  int cur_end = __builtin_amdgcn_readlane(rel, 0);
+
+  bool col_on[NP];
+#pragma unroll
+  for (int p = 0; p < NP; ++p) col_on[p] = (p * 64 + lane) * EPV < dim;
+
+  float acc[NP][EPV];
+#pragma unroll
+  for (int p = 0; p < NP; ++p)
+#pragma unroll
+    for (int c = 0; c < EPV; ++c) acc[p][c] = 0.0f;
+
+  auto next_row = [&]() {
+    ++r;
+    if (r - r_base == 64) {
+      r_base = r;
+      rel = load_rel(r_base);
+    }
+    cur_end = __builtin_amdgcn_readlane(rel, r - r_base);
+  };
+  auto store_y = [&](int row) {
+    T* py = Y + static_cast<int64_t>(row) * ldy;
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+      if (col_on[p]) VecIO<T, EPV>::store(py + (p * 64 + lane) * EPV, acc[p]);
+  };
+  auto store_partial = [&](float* buf) {
+    float* pp = buf + chunk * static_cast<int64_t>(dim);
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+      if (col_on[p]) {
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) pp[(p * 64 + lane) * EPV + c] = acc[p][c];
+      }
+  };
+  auto clear_acc = [&]() {
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) acc[p][c] = 0.0f;
+  };
+  // the row that just ended inside this chunk
+  auto flush_row = [&]() {
+    if (head) store_partial(phead);
+    else store_y(r);
+    head = false;
+    clear_acc();
+  };
+
+  int krel = 0;
+  for (int base = 0; base < L; base += 64) {
+    const int cnt = L - base < 64 ? L - base : 64;
+    int my_col = 0;
+    float my_val = 0.0f;
+    if (lane < cnt) {
+      my_col = colidx[s + base + lane];
+      my_val = vals[s + base + lane];
+    }
+    for (int j = 0; j < cnt; j += U) {
+      float x[U][NP][EPV];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (j + u < cnt) {
+          const int c = __builtin_amdgcn_readlane(my_col, j + u);
+          const T* px = X + static_cast<int64_t>(c) * ldx;
+#pragma unroll
+          for (int p = 0; p < NP; ++p)
+            if (col_on[p]) VecIO<T, EPV>::load(px + (p * 64 + lane) * EPV, x[u][p]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        if (j + u < cnt) {
+          while (krel == cur_end) {
+            flush_row();
+            next_row();
+          }
+          const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_val), j + u));
+#pragma unroll
+          for (int p = 0; p < NP; ++p)
+            if (col_on[p]) {
+#pragma unroll
+              for (int c = 0; c < EPV; ++c) acc[p][c] = __fmaf_rn(v, x[u][p][c], acc[p][c]);
+            }
+          ++krel;
+        }
+      }
+    }
+  }
+
+  // end of the chunk (krel == L): the open row either ends here or runs on
+  int tr = -1;
+  if (cur_end > L) {
+    if (head) {
+      store_partial(phead);  // the whole chunk lies inside one row
+    } else {
+      store_partial(ptail);
+      tr = r;
+    }
+  } else {
+    flush_row();
+    next_row();
+    // empty rows between this chunk's last entry and the next chunk's first
+    while (r < n_rows && cur_end == L) {
+      store_y(r);  // acc is zero
+      next_row();
+    }
+  }
+  if (lane == 0) tail_row[chunk] = tr;
+}
+
+// Adds the pieces of every row that straddles chunk borders, in chunk order.
+template <typename T, int EPV>
+__global__ __launch_bounds__(kSpmmThreads) void spmm_fixup_kernel(
+    const int* __restrict__ chunk_row, const int* __restrict__ tail_row, int64_t nchunks,
+    const float* __restrict__ phead, const float* __restrict__ ptail, T* __restrict__ Y, int64_t ldy, int dim,
+    int n_rows) {
+  const int lane = threadIdx.x & 63;
+  const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + (threadIdx.x >> 6);
+  if (chunk >= nchunks) return;
+  const int r = tail_row[chunk];
+  if (r < 0 || r >= n_rows) return;
+  int64_t last = chunk;  // last chunk that starts inside row r
+  while (last + 1 < nchunks && chunk_row[last + 1] == r) ++last;
+  T* py = Y + static_cast<int64_t>(r) * ldy;
+  for (int col = lane * EPV; col < dim; col += 64 * EPV) {
+    float acc[EPV];
+#pragma unroll
+    for (int c = 0; c < EPV; ++c) acc[c] = ptail[chunk * static_cast<int64_t>(dim) + col + c];
+    int64_t c2 = chunk + 1;
+    for (; c2 + 3 <= last; c2 += 4) {
+      float t[4][EPV];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) t[q][c] = phead[(c2 + q) * static_cast<int64_t>(dim) + col + c];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) acc[c] = acc[c] + t[q][c];
+    }
+    for (; c2 <= last; ++c2)
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) acc[c] = acc[c] + phead[c2 * static_cast<int64_t>(dim) + col + c];
+    VecIO<T, EPV>::store(py + col, acc);
+  }
+}
+
+int64_t spmm_chunks(int64_t nnz) { return nnz <= 0 ? 1 : ceil_div(nnz, kChunk); }
+
+size_t spmm_workspace_bytes(int64_t nnz, int32_t dim) {
+  const int64_t nc = spmm_chunks(nnz);
+  return align_up(static_cast<size_t>(nc) * 2 * sizeof(int), 256) +
+         2 * align_up(static_cast<size_t>(nc) * dim * sizeof(float), 256);
+}
+
+template <typename T, int EPV>
+static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, int64_t ldy, int dim, void* ws,
+                       hipStream_t st) {
+  const int64_t nc = spmm_chunks(A->nnz);
+  char* w = static_cast<char*>(ws);
+  int* chunk_row = reinterpret_cast<int*>(w);
+  int* tail_row = chunk_row + nc;
+  w += align_up(static_cast<size_t>(nc) * 2 * sizeof(int), 256);
+  float* phead = reinterpret_cast<float*>(w);
+  w += align_up(static_cast<size_t>(nc) * dim * sizeof(float), 256);
+  float* ptail = reinterpret_cast<float*>(w);
+
+  chunk_rows_kernel<<<static_cast<unsigned>(ceil_div(A->n_rows, 256)), 256, 0, st>>>(A->rowptr, A->n_rows, chunk_row);
+  CDF_LAUNCH_CHECK("cdf_spmm/chunk_rows");
+  const unsigned nblocks = static_cast<unsigned>(ceil_div(nc, kSpmmWaves));
+  const int per_pass = 64 * EPV;
+  const int np = static_cast<int>(ceil_div(dim, per_pass));
+#define CDF_SPMM_ARGS                                                                                      \
+  <<<nblocks, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, ldy, dim, \
+                                     chunk_row, nc, phead, ptail, tail_row)
+  if (np <= 1) spmm_kernel<T, EPV, 1> CDF_SPMM_ARGS;
+  else if (np <= 2) spmm_kernel<T, EPV, 2> CDF_SPMM_ARGS;
+  else if (np <= 4) spmm_kernel<T, EPV, 4> CDF_SPMM_ARGS;
+  else spmm_kernel<T, EPV, 8> CDF_SPMM_ARGS;
+#undef CDF_SPMM_ARGS
+  CDF_LAUNCH_CHECK("cdf_spmm/main");
+  spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, ldy, dim,
+                                                               A->n_rows);
+  CDF_LAUNCH_CHECK("cdf_spmm/fixup");
+  return CDF_OK;
+}
+
+static int spmm_entry(const char* fn, const cdf_csr* A, const void* X, int64_t ldx, void* Y, int64_t ldy,
+                      int32_t dim, cdf_dtype dt, void* ws, size_t ws_bytes, hipStream_t st) {
+  CDF_REQUIRE(A != nullptr, "%s: matrix is null", fn);
+  CDF_REQUIRE(A->n_rows >= 0 && A->n_cols >= 0 && A->nnz >= 0 && dim > 0 && ldx >= dim && ldy >= dim,
+              "%s: bad shape rows=%d cols=%d nnz=%lld dim=%d ldx=%lld ldy=%lld", fn, A->n_rows, A->n_cols,
+              (long long)A->nnz, dim, (long long)ldx, (long long)ldy);
+  if (dt != CDF_F32 && dt != CDF_BF16) CDF_FAIL(CDF_ERR_UNSUPPORTED, "%s: dtype %d", fn, (int)dt);
+  if (A->n_rows == 0) return CDF_OK;
+  CDF_REQUIRE(A->rowptr && Y && (A->nnz == 0 || (A->colidx && A->vals && X)), "%s: null pointer", fn);
+  const size_t esz = elem_bytes(dt);
+  CDF_REQUIRE(aligned(A->rowptr, 8) && aligned(A->colidx, 4) && aligned(A->vals, 4) && aligned(X, esz) &&
+                  aligned(Y, esz),
+              "%s: misaligned pointer", fn);
+  if (!ws || !aligned(ws, 256) || ws_bytes < spmm_workspace_bytes(A->nnz, dim))
+    CDF_FAIL(CDF_ERR_WORKSPACE, "%s: workspace too small or unaligned (%zu < %zu)", fn, ws_bytes,
+             spmm_workspace_bytes(A->nnz, dim));
+  // widest lane-vector that both operands allow; at most 8 passes of 64 lanes per launch
+  int epv = dt == CDF_BF16 ? 8 : 4;
+  for (; epv > 1; epv >>= 1) {
+    const size_t vb = esz * epv;
+    if (dim % epv == 0 && ldx % epv == 0 && ldy % epv == 0 && aligned(X, vb) && aligned(Y, vb)) break;
+  }
+  const int max_cols = 64 * epv * 8;
+  for (int col0 = 0; col0 < dim; col0 += max_cols) {
+    const int d = dim - col0 < max_cols ? dim - col0 : max_cols;
+    int rc;
+    if (dt == CDF_F32) {
+      const float* x = static_cast<const float*>(X) + col0;
+      float* y = static_cast<float*>(Y) + col0;
+      rc = epv == 4 ? launch_spmm<float, 4>(A, x, ldx, y, ldy, d, ws, st)
+           : epv == 2 ? launch_spmm<float, 2>(A, x, ldx, y, ldy, d, ws, st)
+                      : launch_spmm<float, 1>(A, x, ldx, y, ldy, d, ws, st);
+    } else {
+      const bf16_t* x = static_cast<const bf16_t*>(X) + col0;
+      bf16_t* y = static_cast<bf16_t*>(Y) + col0;
+      rc = epv == 8   ? launch_spmm<bf16_t, 8>(A, x, ldx, y, ldy, d, ws, st)
+           : epv == 4 ? launch_spmm<bf16_t, 4>(A, x, ldx, y, ldy, d, ws, st)
+           : epv == 2 ? launch_spmm<bf16_t, 2>(A, x, ldx, y, ldy, d, ws, st)
+                      : launch_spmm<bf16_t, 1>(A, x, ldx, y, ldy, d, ws, st);
+    }
+    if (rc != CDF_OK) return rc;
+  }
+  return CDF_OK;
+}
+
+}  // namespace cdf
+
+using namespace cdf;
+
+extern "C" int cdf_spmm_fwd(const cdf_csr* A, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t dim,
+                            cdf_dtype dt, void* ws, size_t ws_bytes, void* stream) {
+  return spmm_entry("cdf_spmm_fwd", A, X, ldx, Y, ldy, dim, dt, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int cdf_spmm_bwd(const cdf_csr* At, const void* dY, int64_t ldy, void* dX, int64_t ldx, int32_t dim,
+                            cdf_dtype dt, void* ws, size_t ws_bytes, void* stream) {
+  return spmm_entry("cdf_spmm_bwd", At, dY, ldy, dX, ldx, dim, dt, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}

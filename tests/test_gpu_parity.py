@@ -1,0 +1,407 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+Integer outputs (masks, index lists, codes) and the fp32 sequences the method fixes must
+be bit-equal; aggregated floats within 1e-4 of the row's largest reference magnitude."""
+import numpy as np
+import pytest
+import torch
+
+from cdfgen import configs, features, graphs
+from helpers import assert_rows_close, bf16_to_f32, csr_np
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def cdf():
+    import paper_2408_00232_amd as m
+    m.binding.load()
+    assert torch.cuda.is_available()
+    return m
+
+
+def to_np(t):
+    """Device tensor -> numpy (bf16 as uint16 bit patterns)."""
+    t = t.detach().cpu()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16).copy()
+    return t.numpy().copy()
+
+
+def as_f64(a):
+    return bf16_to_f32(a).astype(np.float64) if a.dtype == np.uint16 else a.astype(np.float64)
+
+
+def make_pair(R, F, ld, dtype, seed, frac_same=0.3, drift=0.08):
+    """cached ~ N(0,1); cur = cached * (1 + drift_r * g), some rows untouched, some cached rows zero."""
+    g = torch.Generator().manual_seed(seed)
+    cached = torch.randn(R, ld, generator=g)
+    rate = torch.rand(R, 1, generator=g) * drift
+    cur = cached * (1 + rate * torch.randn(R, ld, generator=g))
+    same = torch.rand(R, generator=g) < frac_same
+    cur[same] = cached[same]
+    zero = torch.rand(R, generator=g) < 0.05
+    cached[zero] = 0
+    cur, cached = cur.to(dtype), cached.to(dtype)
+    return cur, cached
+
+
+def ws_for(cdf, rows, dim, nnz=1):
+    return torch.zeros(cdf.cdf_workspace_bytes(max(rows, 1), dim, max(nnz, 1)), dtype=torch.uint8, device=DEV)
+
+
+FILTER_SHAPES = [(1000, 128, 128), (1000, 256, 256), (777, 100, 100), (1000, 602, 602), (515, 16, 16),
+                 (300, 1024, 1024), (300, 37, 37), (300, 1, 1), (300, 3, 5), (400, 126, 130), (260, 2000, 2000),
+                 (64, 700, 701)]
+
+
+@pytest.mark.parametrize("R,F,ld", FILTER_SHAPES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("norm", [0, 1])
+def test_cache_filter(cdf, oracle, R, F, ld, dtype, norm):
+    cur, cached = make_pair(R, F, ld, dtype, seed=R * 31 + F)
+    dcur, dcached = cur.to(DEV), cached.to(DEV)
+    mask = torch.full((R,), 7, dtype=torch.uint8, device=DEV)
+    idx = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+    n_sent = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    ws = ws_for(cdf, R, F)
+    ncur, ncached = to_np(cur)[:, :F], to_np(cached)[:, :F]
+    for eps in (0.0, 0.05, 0.5):
+        cdf.cdf_cache_filter(dcur[:, :F], dcached[:, :F], eps, norm, mask, idx, n_sent, ws)
+        torch.cuda.synchronize()
+        omask, oidx = oracle.cache_filter(ncur, ncached, eps, norm)
+        n = int(n_sent.item())
+        assert n == oidx.size
+        np.testing.assert_array_equal(to_np(mask), omask)
+        np.testing.assert_array_equal(to_np(idx)[:n], oidx)
+    assert 0 < oidx.size < R or R < 10
+
+
+def test_cache_filter_edges(cdf, oracle):
+    ws = ws_for(cdf, 1024, 64)
+    n_sent = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    # empty input: count defined, nothing else touched
+    e = torch.zeros(0, 64, device=DEV)
+    cdf.cdf_cache_filter(e, e, 0.1, 0, None, None, n_sent, ws)
+    torch.cuda.synchronize()
+    assert int(n_sent.item()) == 0
+    # all rows sent / none sent, exactly one block and one block plus one row
+    for R in (256, 257):
+        cur = torch.randn(R, 64, device=DEV)
+        mask = torch.zeros(R, dtype=torch.uint8, device=DEV)
+        idx = torch.zeros(R, dtype=torch.int32, device=DEV)
+        cdf.cdf_cache_filter(cur, torch.zeros_like(cur), 0.1, 0, mask, idx, n_sent, ws)
+        torch.cuda.synchronize()
+        assert int(n_sent.item()) == R and torch.equal(idx.cpu(), torch.arange(R, dtype=torch.int32))
+        cdf.cdf_cache_filter(cur, cur.clone(), 0.0, 0, mask, idx, n_sent, ws)
+        torch.cuda.synchronize()
+        assert int(n_sent.item()) == 0 and int(mask.sum().item()) == 0
+
+
+def test_argument_errors(cdf):
+    ws = ws_for(cdf, 64, 64)
+    cur = torch.randn(8, 16, device=DEV)
+    mask = torch.zeros(8, dtype=torch.uint8, device=DEV)
+    idx = torch.zeros(8, dtype=torch.int32, device=DEV)
+    n = torch.zeros(1, dtype=torch.int32, device=DEV)
+    with pytest.raises(cdf.binding.CdfError) as e:
+        cdf.cdf_cache_filter(cur, cur, float("inf"), 0, mask, idx, n, ws)
+    assert e.value.code == cdf.ERR_INVALID_ARG
+    with pytest.raises(cdf.binding.CdfError) as e:
+        cdf.cdf_cache_filter(cur, cur, 0.1, 0, mask, idx, n, ws[:8])
+    assert e.value.code == cdf.ERR_WORKSPACE
+    codes = torch.zeros(8 * 16, dtype=torch.uint8, device=DEV)
+    meta = torch.zeros(8, 2, device=DEV)
+    with pytest.raises(cdf.binding.CdfError) as e:
+        cdf.cdf_quantize(cur, cur.clone(), idx, n, 8, 3, 0, 1, True, codes, meta)
+    assert e.value.code == cdf.ERR_UNSUPPORTED
+    with pytest.raises(cdf.binding.CdfError) as e:
+        cdf.cdf_quantize(cur, None, idx, n, 8, 8, 0, 1, True, codes, meta)
+    assert e.value.code == cdf.ERR_INVALID_ARG
+    torch.cuda.synchronize()
+
+
+QUANT_SHAPES = [(500, 128, 128), (300, 256, 256), (300, 100, 100), (200, 602, 602), (300, 16, 16),
+                (100, 1024, 1024), (200, 37, 37), (200, 1, 1), (200, 3, 5), (100, 2048, 2048), (150, 126, 130)]
+
+
+@pytest.mark.parametrize("R,F,ld", QUANT_SHAPES)
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("bits,qs", [(8, 0), (4, 0), (8, 1), (4, 1), (8, 2)])
+def test_quantize_dequantize(cdf, oracle, R, F, ld, dtype, bits, qs):
+    cur, cached = make_pair(R, F, ld, dtype, seed=R * 17 + F + bits)
+    g = torch.Generator().manual_seed(5)
+    sel = torch.nonzero(torch.rand(R, generator=g) < 0.6).flatten().to(torch.int32)
+    n = sel.numel()
+    rb = cdf.cdf_code_row_bytes(F, bits, qs)
+    for commit, delta in ((1, True), (2, True), (0, False), (2, False)):
+        dcur, dcached = cur.to(DEV), cached.to(DEV)
+        idx = torch.zeros(R, dtype=torch.int32, device=DEV)
+        idx[:n] = sel.to(DEV)
+        n_sent = torch.tensor([n], dtype=torch.int32, device=DEV)
+        codes = torch.full((R * rb + 16,), 0xAB, dtype=torch.uint8, device=DEV)
+        meta = torch.full((R, 2), -7.0, device=DEV)
+        cdf.cdf_quantize(dcur[:, :F], dcached[:, :F], idx, n_sent, R, bits, qs, commit, delta, codes, meta)
+        dst0 = torch.randn(R, ld, generator=g).to(dtype)
+        ddst = dst0.to(DEV)
+        cdf.cdf_dequantize(codes, meta, idx, n_sent, R, bits, qs, ddst[:, :F], accumulate=delta)
+        torch.cuda.synchronize()
+        ncur, ncached = to_np(cur), to_np(cached)
+        ocodes, ometa = oracle.quantize(ncur[:, :F], ncached[:, :F], sel.numpy(), bits, qs, commit, delta)
+        gcodes = to_np(codes)
+        np.testing.assert_array_equal(gcodes[:n * rb].reshape(n, rb), ocodes)
+        assert (gcodes[n * rb:] == 0xAB).all()                      # nothing written past the last message
+        np.testing.assert_array_equal(to_np(meta)[:n], ometa)       # -0.0 == 0.0 here, by value
+        np.testing.assert_array_equal(to_np(dcached), ncached)      # commit, including untouched rows / padding
+        ndst = to_np(dst0)
+        oracle.dequantize(ocodes, ometa, sel.numpy(), ndst[:, :F], bits, qs, accumulate=delta)
+        np.testing.assert_array_equal(to_np(ddst), ndst)
+
+
+def test_quantize_zero_rows(cdf):
+    """*n_sent == 0 on the device: nothing is written."""
+    cur = torch.randn(10, 32, device=DEV)
+    cached = torch.zeros_like(cur)
+    idx = torch.zeros(10, dtype=torch.int32, device=DEV)
+    n_sent = torch.zeros(1, dtype=torch.int32, device=DEV)
+    codes = torch.full((10 * 32,), 9, dtype=torch.uint8, device=DEV)
+    meta = torch.full((10, 2), 3.0, device=DEV)
+    cdf.cdf_quantize(cur, cached, idx, n_sent, 10, 8, 0, 1, True, codes, meta)
+    cdf.cdf_dequantize(codes, meta, idx, n_sent, 10, 8, 0, cur, True)
+    cdf.cdf_quantize(cur, cached, idx, n_sent, 0, 8, 0, 1, True, codes, meta)
+    torch.cuda.synchronize()
+    assert int((codes != 9).sum().item()) == 0 and int((cached != 0).sum().item()) == 0
+
+
+def run_spmm(cdf, rowptr, colidx, vals, n_cols, X, bwd=False):
+    n_rows = rowptr.numel() - 1
+    A = cdf.DeviceCsr(n_rows, n_cols, rowptr, colidx, vals, DEV)
+    ws = ws_for(cdf, n_rows, X.shape[1], colidx.numel())
+    dX = X.to(DEV)
+    Y = torch.full((n_rows, X.shape[1]), 3.0, dtype=X.dtype, device=DEV)
+    (cdf.cdf_spmm_bwd if bwd else cdf.cdf_spmm_fwd)(A.struct, dX, Y, ws)
+    torch.cuda.synchronize()
+    return Y
+
+
+@pytest.mark.parametrize("dim", [128, 256, 100, 602, 16, 37, 1, 1024, 3000])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_spmm_tiny_partition(cdf, oracle, dim, dtype):
+    P = configs.build_partition(configs.TINY)
+    X = features.normal_matrix(3, dim, P.n_loc + P.n_halo, dim).to(dtype)
+    Y = run_spmm(cdf, P.rowptr, P.colidx, P.vals, P.n_loc + P.n_halo, X)
+    want = oracle.spmm(*csr_np(P), P.n_loc + P.n_halo, to_np(X))
+    if dtype == torch.float32:
+        assert_rows_close(to_np(Y), want, what="Y")
+    else:
+        # one bf16 ulp of the oracle's correctly rounded value
+        g, o = as_f64(to_np(Y)), as_f64(want)
+        assert (np.abs(g - o) <= np.maximum(np.abs(o), 1e-30) * 2.0 ** -7).all()
+        assert (to_np(Y) == want).mean() > 0.98
+    dY = features.normal_matrix(4, dim, P.n_loc, dim).to(dtype)
+    dXg = run_spmm(cdf, P.t_rowptr, P.t_colidx, P.t_vals, P.n_loc, dY, bwd=True)
+    wantT = oracle.spmm(*csr_np(P, True), P.n_loc, to_np(dY))
+    if dtype == torch.float32:
+        assert_rows_close(to_np(dXg), wantT, what="dX")
+    else:
+        g, o = as_f64(to_np(dXg)), as_f64(wantT)
+        assert (np.abs(g - o) <= np.maximum(np.abs(o), 1e-30) * 2.0 ** -7).all()
+
+
+def test_spmm_long_and_empty_rows(cdf, oracle):
+    """Rows of 0, 1, 255, 256, 257 and several thousand entries, empty rows at the start, at the
+    end and exactly on chunk borders; run twice for bit-reproducibility."""
+    rs = np.random.default_rng(21)
+    lens = [0, 0, 1, 255, 0, 256, 0, 0, 257, 3, 5000, 0, 254, 2, 1, 1, 700, 0, 0, 1280, 0, 31, 0, 0]
+    n_cols = 4000
+    rowptr = np.zeros(len(lens) + 1, np.int64)
+    rowptr[1:] = np.cumsum(lens)
+    colidx = np.concatenate([np.sort(rs.choice(n_cols, l, replace=l > n_cols)) for l in lens]).astype(np.int32)
+    vals = rs.standard_normal(colidx.size).astype(np.float32)
+    for dim in (128, 100, 602):
+        X = torch.from_numpy(rs.standard_normal((n_cols, dim)).astype(np.float32))
+        args = (torch.from_numpy(rowptr), torch.from_numpy(colidx), torch.from_numpy(vals), n_cols, X)
+        Y1 = run_spmm(cdf, *args)
+        Y2 = run_spmm(cdf, *args)
+        assert torch.equal(Y1, Y2)
+        want = oracle.spmm(rowptr, colidx, vals, n_cols, X.numpy())
+        assert_rows_close(to_np(Y1), want, what=f"Y dim {dim}")
+        assert int((Y1[[0, 1, 4, 6, 7, 11, 17, 18, 20, 22, 23]] != 0).sum().item()) == 0
+    # a matrix with no entries at all
+    Y = run_spmm(cdf, torch.zeros(6, dtype=torch.int64), torch.zeros(0, dtype=torch.int32),
+                 torch.zeros(0), n_cols, X)
+    assert int((Y != 0).sum().item()) == 0
+
+
+DENSE_SHAPES = [(1000, 100, 47), (300, 602, 256), (513, 16, 8), (700, 128, 256), (257, 256, 41), (130, 64, 64),
+                (5000, 128, 16), (64, 33, 130)]
+
+
+@pytest.mark.parametrize("n,f,g", DENSE_SHAPES)
+@pytest.mark.parametrize("relu", [True, False])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_dense_fwd_bwd(cdf, oracle, n, f, g, relu, dtype):
+    M = features.normal_matrix(7, n + f, n, f).to(dtype)
+    W = features.glorot(7, g, f, g)
+    dH = features.normal_matrix(8, n + g, n, g)
+    dM_, dW_, dH_, W_ = M.to(DEV), None, dH.to(DEV), W.to(DEV)
+    Z = torch.zeros(n, g, device=DEV)
+    H = torch.zeros(n, g, device=DEV)
+    cdf.cdf_dense_fwd(dM_, W_, relu, Z, H)
+    torch.cuda.synchronize()
+    oZ, oH = oracle.dense_fwd(to_np(M), W.numpy(), relu)
+    assert_rows_close(to_np(Z), oZ, what="Z")
+    assert_rows_close(to_np(H), oH, rel=1e-4, frob=1e-5, what="H")
+    # backward from the oracle's own Z (an input of this entry point), so the sign test is shared
+    Zs = torch.from_numpy(oZ).to(DEV)
+    dW = torch.zeros(f, g, device=DEV)
+    dM = torch.zeros(n, f, dtype=dtype, device=DEV)
+    ws = ws_for(cdf, n, max(f, g))
+    cdf.cdf_dense_bwd(dM_, W_, Zs, dH_, relu, dW, dM, ws)
+    dW2 = torch.zeros(f, g, device=DEV)
+    cdf.cdf_dense_bwd(dM_, W_, Zs, dH_, relu, dW2, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dW, dW2)
+    odW, odM = oracle.dense_bwd(to_np(M), W.numpy(), oZ, dH.numpy(), relu)
+    assert_rows_close(to_np(dW), odW, what="dW")
+    if dtype == torch.float32:
+        assert_rows_close(to_np(dM), odM, what="dM")
+    else:
+        gm, om = as_f64(to_np(dM)), as_f64(odM)
+        assert (np.abs(gm - om) <= np.maximum(np.abs(om), 1e-30) * 2.0 ** -7 + 1e-30).all()
+
+
+def layer_case(cdf, oracle, P, f_in, f_out, eps, norm, bits, qs, commit, delta, relu, epochs, dtype=torch.float32,
+               seed=1):
+    """Forward + backward of one layer for several epochs, oracle run beside it from the same
+    inputs. The halo stream is an input, so the forward cache state stays bit-equal."""
+    A = cdf.DeviceCsr(P.n_loc, P.n_loc + P.n_halo, P.rowptr, P.colidx, P.vals, DEV)
+    At = cdf.DeviceCsr(P.n_loc + P.n_halo, P.n_loc, P.t_rowptr, P.t_colidx, P.t_vals, DEV)
+    L = cdf.LayerBuffers(A, At, P.n_loc, P.n_halo, f_in, f_out, dtype=dtype, bits=bits, qs=qs, device=DEV)
+    ws = torch.zeros(L.workspace_bytes(), dtype=torch.uint8, device=DEV)
+    x_loc = features.normal_matrix(seed, 1, P.n_loc, f_in).to(dtype)
+    W = features.glorot(seed, 2, f_in, f_out)
+    stream = features.HaloStream(seed, P.n_halo, f_in)
+    L.xfull[:P.n_loc] = x_loc.to(DEV)
+    L.W.copy_(W)
+    o_x = np.concatenate([to_np(x_loc), np.zeros((P.n_halo, f_in), to_np(x_loc).dtype)])
+    o_sent = np.zeros_like(o_x[P.n_loc:])
+    An, Atn = csr_np(P), csr_np(P, True)
+    rates = []
+    for t in range(epochs):
+        fresh = stream.value().to(dtype)
+        dH = features.normal_matrix(seed, 50 + t, P.n_loc, f_out)
+        L.halo_fresh.copy_(fresh)
+        L.dH.copy_(dH)
+        cdf.cdf_gcn_layer_fwd(L.fwd_args(eps, norm, commit, delta, relu), ws)
+        torch.cuda.synchronize()
+        of = oracle.layer_fwd(An, P.n_loc, P.n_halo, o_x, to_np(fresh), o_sent, W.numpy(), eps, norm, bits, qs,
+                              commit, relu, delta)
+        n = int(L.n_sent.item())
+        rates.append(n / max(P.n_halo, 1))
+        assert n == of["idx"].size
+        np.testing.assert_array_equal(to_np(L.mask)[:P.n_halo], of["mask"])
+        np.testing.assert_array_equal(to_np(L.idx)[:n], of["idx"])
+        np.testing.assert_array_equal(to_np(L.codes)[:n * L.row_bytes].reshape(n, -1), of["codes"])
+        np.testing.assert_array_equal(to_np(L.meta)[:n], of["meta"])
+        np.testing.assert_array_equal(to_np(L.cache_sent), o_sent)
+        np.testing.assert_array_equal(to_np(L.xfull), o_x)
+        if dtype == torch.float32:
+            assert_rows_close(to_np(L.M), of["M"], what="M")
+        if dtype == torch.float32:
+            assert_rows_close(to_np(L.Z), of["Z"], what="Z")
+            assert_rows_close(to_np(L.H), of["H"], what="H")
+        else:
+            assert_rows_close(to_np(L.Z), of["Z"], rel=1e-2, frob=1e-2, what="Z")
+        # backward: fed with the oracle's forward results and a gradient cache built from the
+        # oracle's halo gradients so that every row sits well away from the threshold
+        ob0 = oracle.dense_bwd(of["M"], W.numpy(), of["Z"], dH.numpy(), relu)
+        odx = oracle.spmm(*Atn, P.n_loc, ob0[1])
+        gh = as_f64(odx[P.n_loc:])
+        rs = np.random.default_rng(seed + t)
+        keep = rs.random(P.n_halo) < (0.5 if eps > 0 else -1.0)   # threshold 0: any difference is sent
+        factor = np.where(keep, 1.0 + eps * 0.25, 1.0 + eps * 4.0 + 0.5)[:, None]
+        gsent = torch.from_numpy((gh * factor).astype(np.float32)).to(dtype)
+        L.M.copy_(torch.from_numpy(of["M"]).view(L.M.dtype) if dtype == torch.float32 else
+                  torch.from_numpy(of["M"].view(np.int16)).view(torch.bfloat16))
+        L.Z.copy_(torch.from_numpy(of["Z"]))
+        L.gcache_sent.copy_(gsent)
+        cdf.cdf_gcn_layer_bwd(L.bwd_args(eps, norm, commit, delta, relu), ws)
+        torch.cuda.synchronize()
+        o_gsent = to_np(gsent)
+        ob = oracle.layer_bwd(Atn, P.n_loc, P.n_halo, of["M"], of["Z"], dH.numpy(), W.numpy(), o_gsent, eps, norm,
+                              bits, qs, commit, relu, True, delta)
+        assert_rows_close(to_np(L.dW), ob["dW"], what="dW")
+        if dtype == torch.float32:
+            assert_rows_close(to_np(L.dM), ob["dM"], what="dM")
+            assert_rows_close(to_np(L.dxfull), ob["dxfull"], what="dxfull")
+        gn = int(L.gn_sent.item())
+        np.testing.assert_array_equal(to_np(L.gmask)[:P.n_halo], ob["mask"])
+        np.testing.assert_array_equal(to_np(L.gidx)[:gn], ob["idx"])
+        if eps > 0:
+            nz = np.abs(gh).max(1) > 0
+            np.testing.assert_array_equal(ob["mask"][nz], (~keep[nz]).astype(np.uint8))
+        if qs != 2 and gn and dtype == torch.float32:
+            # codes come from gradients that differ in the last bits between the two sides: a code
+            # may move by one step where the value sits on a rounding border
+            gc = to_np(L.gcodes)[:gn * L.row_bytes].reshape(gn, -1).astype(np.int32)
+            oc = ob["codes"].astype(np.int32)
+            if bits == 4:
+                gc = np.stack([gc & 15, gc >> 4], -1).reshape(gn, -1)
+                oc = np.stack([oc & 15, oc >> 4], -1).reshape(gn, -1)
+            if qs == 1:
+                sgn = 1 << (bits - 1)
+                gc, oc = (gc ^ sgn) - sgn, (oc ^ sgn) - sgn
+            assert np.abs(gc - oc).max() <= 1 and (gc != oc).mean() < 0.01
+            np.testing.assert_allclose(to_np(L.gmeta)[:gn], ob["meta"], rtol=1e-4, atol=1e-30)
+        stream.advance()
+    return rates
+
+
+def test_layer_tiny_paper_setting(cdf, oracle):
+    w = configs.TINY
+    P = configs.build_partition(w)
+    rates = layer_case(cdf, oracle, P, 128, 16, w.eps, 0, 8, 0, 1, True, True, epochs=3)
+    assert rates[0] > 0.99 and rates[-1] < rates[0]
+    layer_case(cdf, oracle, P, 16, 8, w.eps, 0, 8, 0, 1, True, False, epochs=3)
+
+
+def test_layer_tiny_l2_symmetric(cdf, oracle):
+    P = configs.build_partition(configs.TINY)
+    layer_case(cdf, oracle, P, 128, 16, 0.05, 1, 8, 1, 1, True, True, epochs=3)
+
+
+@pytest.mark.parametrize("part", [1, 3])
+def test_layer_tiny_other_partitions_4bit_deq_commit(cdf, oracle, part):
+    P = configs.build_partition(configs.TINY, part=part)
+    layer_case(cdf, oracle, P, 128, 16, 0.05, 0, 4, 0, 2, True, True, epochs=3)
+
+
+def test_layer_eps_zero_is_uncached(cdf, oracle):
+    """Threshold 0 with value messages: the halo rows the aggregation reads are bit-equal to
+    the fresh rows, so the step equals the uncached one on the same kernels."""
+    P = configs.build_partition(configs.TINY)
+    rates = layer_case(cdf, oracle, P, 128, 16, 0.0, 0, 8, 2, 1, False, True, epochs=3)
+    assert all(r > 0.99 for r in rates)
+
+
+def test_layer_mid_shrunk(cdf, oracle):
+    w = configs.shrink(configs.MID, 12000)
+    P = configs.build_partition(w)
+    assert P.nnz > 30000 and P.n_halo > 2000
+    layer_case(cdf, oracle, P, 602, 256, 0.01, 0, 8, 0, 1, True, True, epochs=2)
+    layer_case(cdf, oracle, P, 256, 41, 0.1, 0, 8, 0, 1, True, False, epochs=2)
+
+
+def test_layer_large_shrunk_bfs(cdf, oracle):
+    w = configs.shrink(configs.LARGE, 20000)
+    P = configs.build_partition(w)
+    layer_case(cdf, oracle, P, 100, 256, 0.05, 0, 8, 0, 1, True, True, epochs=2)
+    layer_case(cdf, oracle, P, 256, 47, 0.05, 0, 8, 0, 1, True, False, epochs=1)
+
+
+def test_layer_wide_shrunk_bf16_4bit(cdf, oracle):
+    w = configs.shrink(configs.WIDE, 4096)
+    P = configs.build_partition(w)
+    layer_case(cdf, oracle, P, 1024, 512, 0.05, 0, 4, 0, 1, True, True, epochs=2, dtype=torch.bfloat16)

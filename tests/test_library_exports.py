@@ -1,0 +1,71 @@
+"""The C-ABI library loads on a machine without a GPU and exports every entry point the
+header declares; host-only calls behave; the binding lists the same names."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2408_00232_amd import binding, build
+    if not os.path.exists(binding.LIB_PATH):
+        build.build_lib(verbose=False)
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cdf.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cdf_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2408_00232_amd import binding
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert getattr(lib, n) is not None
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_host_only_calls(lib):
+    from paper_2408_00232_amd import binding as B
+    assert B.cdf_code_row_bytes(100, 8, B.Q_MINMAX) == 100
+    assert B.cdf_code_row_bytes(101, 4, B.Q_MINMAX) == 51
+    assert B.cdf_code_row_bytes(7, 8, B.Q_NONE) == 28
+    small = B.cdf_workspace_bytes(1000, 128, 10_000)
+    big = B.cdf_workspace_bytes(1_000_000, 256, 100_000_000)
+    assert 0 < small < big and small % 256 == 0
+    # argument validation happens on the host, before any launch
+    rc = lib.cdf_cache_filter(None, None, ctypes.c_int32(-1), ctypes.c_int32(4), ctypes.c_int64(4), 0,
+                              ctypes.c_float(0.1), 0, None, None, None, None, ctypes.c_size_t(0), None)
+    assert rc == B.ERR_INVALID_ARG and b"cdf_cache_filter" in lib.cdf_last_error()
+    rc = lib.cdf_quantize(None, None, None, None, ctypes.c_int32(4), ctypes.c_int32(4), ctypes.c_int64(4), 0, 5, 0, 0, 0,
+                          None, None, None)
+    assert rc == B.ERR_UNSUPPORTED
+
+
+def test_binding_structs_match_header_layout():
+    """Field order of the ctypes argument blocks follows the header's structs."""
+    from paper_2408_00232_amd import binding as B
+    text = open(os.path.join(ROOT, "include", "cdf.h")).read()
+    for name, cls in (("cdf_layer_fwd_args", B.cdf_layer_fwd_args), ("cdf_layer_bwd_args", B.cdf_layer_bwd_args),
+                      ("cdf_csr", B.cdf_csr)):
+        end = re.search(r"\}\s*" + name + ";", text).start()
+        body = text[text.rindex("typedef struct {", 0, end) + len("typedef struct {"):end]
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        fields = []
+        for decl in body.split(";"):
+            decl = decl.strip()
+            if not decl:
+                continue
+            parts = decl.split(",")
+            first = re.findall(r"[A-Za-z_][A-Za-z0-9_]*", parts[0])[-1]
+            fields.append(first)
+            for extra in parts[1:]:
+                fields.append(re.findall(r"[A-Za-z_][A-Za-z0-9_]*", extra)[-1])
+        assert fields == [f[0] for f in cls._fields_], name
