@@ -33,6 +33,15 @@ def as_f64(a):
     return bf16_to_f32(a).astype(np.float64) if a.dtype == np.uint16 else a.astype(np.float64)
 
 
+def assert_bf16_close(got, want, what=""):
+    """bf16 outputs: within one bf16 step of the oracle's correctly rounded value, plus the
+    fp32-accumulation allowance (1e-4 of the row's largest magnitude) where sums cancel."""
+    g, o = as_f64(got), as_f64(want)
+    rowmax = np.maximum(np.abs(o).max(1, keepdims=True), 1e-30)
+    bad = np.abs(g - o) > np.abs(o) * 2.0 ** -7 + 1e-4 * rowmax
+    assert not bad.any(), f"{what}: {int(bad.sum())} elements off"
+
+
 def make_pair(R, F, ld, dtype, seed, frac_same=0.3, drift=0.08):
     """cached ~ N(0,1); cur = cached * (1 + drift_r * g), some rows untouched, some cached rows zero."""
     g = torch.Generator().manual_seed(seed)
@@ -195,9 +204,7 @@ def test_spmm_tiny_partition(cdf, oracle, dim, dtype):
     if dtype == torch.float32:
         assert_rows_close(to_np(Y), want, what="Y")
     else:
-        # one bf16 ulp of the oracle's correctly rounded value
-        g, o = as_f64(to_np(Y)), as_f64(want)
-        assert (np.abs(g - o) <= np.maximum(np.abs(o), 1e-30) * 2.0 ** -7).all()
+        assert_bf16_close(to_np(Y), want, "Y")
         assert (to_np(Y) == want).mean() > 0.98
     dY = features.normal_matrix(4, dim, P.n_loc, dim).to(dtype)
     dXg = run_spmm(cdf, P.t_rowptr, P.t_colidx, P.t_vals, P.n_loc, dY, bwd=True)
@@ -205,8 +212,7 @@ def test_spmm_tiny_partition(cdf, oracle, dim, dtype):
     if dtype == torch.float32:
         assert_rows_close(to_np(dXg), wantT, what="dX")
     else:
-        g, o = as_f64(to_np(dXg)), as_f64(wantT)
-        assert (np.abs(g - o) <= np.maximum(np.abs(o), 1e-30) * 2.0 ** -7).all()
+        assert_bf16_close(to_np(dXg), wantT, "dX")
 
 
 def test_spmm_long_and_empty_rows(cdf, oracle):
@@ -268,8 +274,7 @@ def test_dense_fwd_bwd(cdf, oracle, n, f, g, relu, dtype):
     if dtype == torch.float32:
         assert_rows_close(to_np(dM), odM, what="dM")
     else:
-        gm, om = as_f64(to_np(dM)), as_f64(odM)
-        assert (np.abs(gm - om) <= np.maximum(np.abs(om), 1e-30) * 2.0 ** -7 + 1e-30).all()
+        assert_bf16_close(to_np(dM), odM, "dM")
 
 
 def layer_case(cdf, oracle, P, f_in, f_out, eps, norm, bits, qs, commit, delta, relu, epochs, dtype=torch.float32,
