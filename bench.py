@@ -1,0 +1,233 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-partition GCN layer step on one MI355X.
+
+A step = the whole hot path over the model of the chosen workload: for every layer the
+forward step (cache test, message build, recovery, aggregation, dense transform) and the
+backward step (dense gradients, transposed aggregation, cache test and message build on the
+halo gradients). value = edges traversed per second = layers * nnz / step time, inputs
+resident in HBM. One JSON line on stdout; progress on stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def spmm_bytes(rows_out, rows_in, nnz, dim, esz):
+    """Algorithmic bytes of one aggregation launch: the CSR arrays, every needed input row once,
+    every output row once (compulsory traffic), and the same with no reuse of input rows."""
+    csr = 8 * (rows_out + 1) + 8 * nnz
+    out = rows_out * dim * esz
+    return csr + out + rows_in * dim * esz, csr + out + nnz * dim * esz
+
+
+def cpu_baseline(model, budget_edges=4_000_000):
+    """The oracle, as it stands, on a bounded sample of the same workload: every k-th local row of
+    the partition (with all columns those rows touch), one stationary step of all layers."""
+    import numpy as np
+    import torch
+    import oracle
+
+    P, w = model.P, model.w
+    oracle.build()
+    cores = min(os.cpu_count() or 1, 16)
+    oracle.set_threads(cores)
+    stride = max(1, int(round(P.nnz / budget_edges)))
+    rows = torch.arange(0, P.n_loc, stride, device=P.rowptr.device)
+    lens = (P.rowptr[rows + 1] - P.rowptr[rows])
+    ptr = torch.zeros(rows.numel() + 1, dtype=torch.int64, device=rows.device)
+    torch.cumsum(lens, 0, out=ptr[1:])
+    nnz_s = int(ptr[-1])
+    seg = torch.repeat_interleave(torch.arange(rows.numel(), device=rows.device), lens)
+    pos = torch.arange(nnz_s, device=rows.device) - ptr[seg] + P.rowptr[rows][seg]
+    cols = P.colidx[pos].long()
+    vals = P.vals[pos]
+    # local ids: sampled rows first (they stay "local"), every other touched column is halo
+    n_s = rows.numel()
+    lid = torch.full((P.n_loc + P.n_halo,), -1, dtype=torch.int64, device=rows.device)
+    lid[rows] = torch.arange(n_s, device=rows.device)
+    other = torch.unique(cols[lid[cols] < 0])
+    lid[other] = n_s + torch.arange(other.numel(), device=rows.device)
+    h_s = other.numel()
+    lc = lid[cols]
+    order = torch.argsort(seg * (n_s + h_s) + lc)
+    A = (ptr.cpu().numpy(), lc[order].to(torch.int32).cpu().numpy(), vals[order].cpu().numpy())
+    order_t = torch.argsort(lc * n_s + seg)
+    tptr = torch.zeros(n_s + h_s + 1, dtype=torch.int64, device=rows.device)
+    torch.cumsum(torch.bincount(lc, minlength=n_s + h_s), 0, out=tptr[1:])
+    At = (tptr.cpu().numpy(), seg[order_t].to(torch.int32).cpu().numpy(), vals[order_t].cpu().numpy())
+    qs = {"minmax": oracle.Q_MINMAX, "symmetric": oracle.Q_SYMMETRIC, "none": oracle.Q_NONE}[w.qscheme]
+    norm = {"linf": oracle.NORM_LINF, "l2": oracle.NORM_L2}[w.norm]
+
+    def host(t):
+        t = t.detach().cpu()
+        if t.dtype == torch.bfloat16:
+            return t.view(torch.int16).numpy().view(np.uint16).copy()
+        return t.numpy().copy()
+
+    # inputs of the sample: local rows from xfull, "halo" rows from the full xfull rows the sample
+    # touches; their two alternating versions are the same matrix (local part) or the fresh versions
+    state = []
+    for li, L in enumerate(model.layers):
+        I = model.inputs[li]
+        full = [torch.cat([L.xfull[:P.n_loc], I.fresh[v]]) for v in range(2)]
+        fresh = [host(f[other]) for f in full]
+        x = np.concatenate([host(L.xfull[rows]), np.zeros_like(fresh[0])])
+        state.append(dict(x=x, fresh=fresh, sent=np.zeros_like(fresh[0]), gsent=np.zeros_like(fresh[0]),
+                          W=host(L.W), dH=[host(I.dH[v][rows]) for v in range(2)]))
+        del full
+    nl = len(model.layers)
+
+    def step(v):
+        outs = []
+        for li in range(nl):
+            s = state[li]
+            outs.append(oracle.layer_fwd(A, n_s, h_s, s["x"], s["fresh"][v], s["sent"], s["W"], w.eps, norm,
+                                         w.bits, qs, oracle.COMMIT_CUR, li + 1 < nl, True))
+        for li in reversed(range(nl)):
+            s = state[li]
+            oracle.layer_bwd(At, n_s, h_s, outs[li]["M"], outs[li]["H"], s["dH"][v], s["W"], s["gsent"], w.eps,
+                             norm, w.bits, qs, oracle.COMMIT_CUR, li + 1 < nl, True, True)
+
+    step(0)                       # fills the caches (everything is sent once), not timed
+    t0 = time.perf_counter()
+    step(1)
+    dt = time.perf_counter() - t0
+    return {"value": nl * nnz_s / dt / 1e9, "unit": "GE/s", "cores": oracle.get_threads(), "kind": "oracle",
+            "sample": f"every {stride}th local row of the partition: {n_s} rows, {h_s} other columns, "
+                      f"{nnz_s} edges, all {nl} layers fwd+bwd, one stationary step in {dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="share", help="tiny | mid | large | wide | share")
+    ap.add_argument("--rho", type=float, default=0.37, help="fraction of halo rows refreshed per step")
+    ap.add_argument("--phi", type=float, default=0.01, help="fraction of local rows whose gradient changes")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run the library's plain copy kernel on 1 GiB (for scaling hardware counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build runs on one GPU only (no collectives are part of it); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    from cdfgen import configs
+    import paper_2408_00232_amd as cdf
+    from paper_2408_00232_amd.workload import Model
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    cdf.binding.load()
+    dev = "cuda:0"
+    w = configs.ALL[args.workload]
+    t_setup = time.time()
+    log(f"[bench] building workload '{w.name}' on {dev} ...")
+    model = Model(w, dev, rho=args.rho, phi=args.phi)
+    torch.cuda.synchronize()
+    log(f"[bench] partition: n_loc={model.n_loc} n_halo={model.n_halo} nnz={model.nnz} "
+        f"layers={w.layers()} setup {time.time() - t_setup:.1f}s "
+        f"mem {torch.cuda.memory_allocated() / 2**30:.1f} GiB")
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.zeros_like(src)
+        for _ in range(3):
+            cdf.cdf_profile_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
+    for t in range(args.warmup):
+        model.step(t)
+    torch.cuda.synchronize()
+    log("[bench] warmup done")
+
+    cdf.cdf_profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(args.warmup, args.warmup + args.steps):
+        model.step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    cdf.cdf_profile_enable(False)
+
+    ms_per_step = elapsed / args.steps * 1e3
+    ges = model.edges_per_step() / (elapsed / args.steps) / 1e9
+
+    # per-kernel durations from the events recorded inside the timed region
+    kernels = {}
+    spmm_ms = []
+    for k in range(cdf.cdf_profile_kernels()):
+        ms = cdf.cdf_profile_read(k)
+        if ms:
+            name = cdf.cdf_profile_kernel_name(k)
+            kernels[name] = {"launches": len(ms), "avg_ms": sum(ms) / len(ms),
+                             "ms_per_step": sum(ms) / args.steps}
+            if name == "spmm_kernel":
+                spmm_ms = ms
+    # dominant kernel: the aggregation. Launch order within a step: forward layers 0..L-1 on A,
+    # then backward layers L-1..0 on A^T; algorithmic bytes differ per launch (feature width).
+    esz = 2 if w.dtype == "bf16" else 4
+    n, h, nnz = model.n_loc, model.n_halo, model.nnz
+    per_step = [spmm_bytes(n, n + h, nnz, f, esz) for f, _ in w.layers()] + \
+               [spmm_bytes(n + h, n, nnz, f, esz) for f, _ in reversed(w.layers())]
+    nl = len(per_step)
+    roof = None
+    if spmm_ms and len(spmm_ms) == nl * args.steps:
+        bmin = sum(b[0] for b in per_step) / nl
+        bmax = sum(b[1] for b in per_step) / nl
+        avg_s = sum(spmm_ms) / len(spmm_ms) / 1e3
+        # achieved: the aggregation's algorithmic bytes - per stored entry 8 bytes of CSR plus one
+        # feature row (dim * element size), plus row pointers and the output rows - over the
+        # average launch time. compulsory_*: the same with every input row counted once only.
+        roof = {"kernel": "spmm_kernel", "bound": "hbm", "achieved": bmax / avg_s / 1e9, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": bmax / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                "avg_launch_ms": avg_s * 1e3, "algorithmic_bytes_per_launch": bmax,
+                "compulsory_bytes_per_launch": bmin, "compulsory_GBps": bmin / avg_s / 1e9,
+                "launch_ms_by_position": [sum(spmm_ms[i::nl]) / args.steps for i in range(nl)],
+                "algorithmic_GBps_by_position": [per_step[i][1] / (sum(spmm_ms[i::nl]) / args.steps) / 1e6
+                                                 for i in range(nl)]}
+        tfile = os.path.join(ROOT, "profiles", f"traffic_{w.name}.txt")
+        if os.path.exists(tfile):
+            for line in open(tfile):
+                if line.startswith("spmm_kernel ="):
+                    f_b, w_b = line.split("=")[1].split()
+                    roof["traffic"] = float(f_b) + float(w_b)
+
+    rho_f = [int(L.n_sent.item()) / max(h, 1) for L in model.layers]
+    rho_b = [int(L.gn_sent.item()) / max(h, 1) for L in model.layers]
+
+    out = {
+        "metric": "GCN layer fwd+bwd edges/sec (GE/s) per partition; % of HBM roofline",
+        "value": ges, "unit": "GE/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.kind} graph, {w.n_vertices} vertices, partition {w.part} of "
+                               f"{w.parts} ({w.partitioner}), n_loc={n}, n_halo={h}, nnz={nnz}, layers "
+                               f"{'-'.join(str(d) for d in w.dims)}, {w.bits}-bit {w.qscheme} messages, "
+                               f"eps={w.eps} ({w.norm})",
+                   "edges_per_step": model.edges_per_step(), "send_fraction_fwd": rho_f,
+                   "send_fraction_bwd": rho_b},
+        "roofline": roof,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a sample ...")
+        out["cpu_baseline"] = cpu_baseline(model)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

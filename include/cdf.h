@@ -67,6 +67,26 @@ typedef struct {
 /* Host-side text of the last error raised on the calling thread ("" if none). */
 const char* cdf_last_error(void);
 
+/*
+ * Optional per-kernel timing for benchmarks (host functions, not thread safe). While
+ * enabled, every kernel launch of the library is bracketed by a pair of HIP events on the
+ * launch stream (default-priority events, no device memory). cdf_profile_enable(1) clears
+ * earlier records; cdf_profile_read() waits for the recorded launches of one kernel id
+ * (0 .. cdf_profile_kernels()-1) and writes their durations in milliseconds, in launch order,
+ * to the HOST array ms[cap]; it returns the number of launches recorded (may exceed cap),
+ * or a negative status. At most 8192 launches are kept per session.
+ */
+int cdf_profile_enable(int on);
+int cdf_profile_kernels(void);
+const char* cdf_profile_kernel_name(int kernel);
+int cdf_profile_read(int kernel, float* ms /* host */, int cap);
+
+/* A plain device-to-device copy kernel (16 bytes per lane, grid-stride) of `bytes` bytes
+ * (multiple of 16, both pointers 16-byte aligned). It exists so that hardware counter
+ * readings of the other kernels can be scaled by what the same counters report for a
+ * transfer of known size. */
+int cdf_profile_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 /* Bytes of workspace that cover any call on matrices of at most max_rows rows (of a
  * feature matrix or of a CSR operand, whichever is larger), max_dim columns and
  * max_nnz stored entries. Host function, no device work. */

@@ -19,7 +19,8 @@ Q_MINMAX, Q_SYMMETRIC, Q_NONE = 0, 1, 2
 COMMIT_NONE, COMMIT_CUR, COMMIT_DEQ = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
-EXPORTS = ["cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_quantize",
+EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf_profile_kernel_name", "cdf_profile_read",
+           "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_quantize",
            "cdf_dequantize", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
            "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd"]
 
@@ -74,6 +75,7 @@ def load():
         lib.cdf_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int64]
         lib.cdf_code_row_bytes.restype = ctypes.c_size_t
         lib.cdf_code_row_bytes.argtypes = [ctypes.c_int32, ctypes.c_int, ctypes.c_int]
+        lib.cdf_profile_kernel_name.restype = ctypes.c_char_p
         _lib = lib
     return _lib
 
@@ -112,6 +114,33 @@ def make_csr(n_rows, n_cols, rowptr, colidx, vals) -> cdf_csr:
     assert rowptr.dtype == torch.int64 and colidx.dtype == torch.int32 and vals.dtype == torch.float32
     assert rowptr.numel() == n_rows + 1
     return cdf_csr(n_rows, n_cols, colidx.numel(), rowptr.data_ptr(), colidx.data_ptr(), vals.data_ptr())
+
+
+def cdf_profile_enable(on: bool) -> None:
+    _check("cdf_profile_enable", load().cdf_profile_enable(ctypes.c_int(1 if on else 0)))
+
+
+def cdf_profile_kernels() -> int:
+    return int(load().cdf_profile_kernels())
+
+
+def cdf_profile_kernel_name(kernel: int) -> str:
+    return load().cdf_profile_kernel_name(ctypes.c_int(kernel)).decode()
+
+
+def cdf_profile_read(kernel: int, cap: int = 8192):
+    """Durations (ms) of the recorded launches of one kernel, in launch order."""
+    buf = (ctypes.c_float * cap)()
+    n = load().cdf_profile_read(ctypes.c_int(kernel), buf, ctypes.c_int(cap))
+    if n < 0:
+        _check("cdf_profile_read", n)
+    return [buf[i] for i in range(min(n, cap))]
+
+
+def cdf_profile_copy(dst, src) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= nbytes
+    _check("cdf_profile_copy", load().cdf_profile_copy(_ptr(dst), _ptr(src), ctypes.c_size_t(nbytes), _stream()))
 
 
 def cdf_workspace_bytes(max_rows: int, max_dim: int, max_nnz: int) -> int:

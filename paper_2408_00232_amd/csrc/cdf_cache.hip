@@ -226,7 +226,7 @@ extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_r
   if (n_rows == 0) {
     // nothing to test: the count is still defined (written by a kernel, not a memset node,
     // so that the call can be captured into a graph)
-    scan_kernel<<<1, 1024, 0, st>>>(nullptr, 0, nullptr, n_sent);
+    { ProfScope ps(K_SCAN, st); scan_kernel<<<1, 1024, 0, st>>>(nullptr, 0, nullptr, n_sent); }
     CDF_LAUNCH_CHECK("cdf_cache_filter/scan");
     return CDF_OK;
   }
@@ -246,6 +246,7 @@ extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_r
   const int glog = nvec >= 64 ? 6 : log2_ceil(nvec);
 #define CDF_FILTER_CASE(T, E)                                                                       \
   launch_filter<T, E>(cur, cached, n_rows, dim, ld, eps, norm, glog, mask, counts, nblocks, st)
+  prof_begin(K_FILTER, st);
   if (dt == CDF_F32) {
     if (epv == 4) CDF_FILTER_CASE(float, 4);
     else if (epv == 2) CDF_FILTER_CASE(float, 2);
@@ -256,10 +257,11 @@ extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_r
     else CDF_FILTER_CASE(bf16_t, 1);
   }
 #undef CDF_FILTER_CASE
+  prof_end(K_FILTER, st);
   CDF_LAUNCH_CHECK("cdf_cache_filter/filter");
-  scan_kernel<<<1, 1024, 0, st>>>(counts, nblocks, offsets, n_sent);
+  { ProfScope ps(K_SCAN, st); scan_kernel<<<1, 1024, 0, st>>>(counts, nblocks, offsets, n_sent); }
   CDF_LAUNCH_CHECK("cdf_cache_filter/scan");
-  compact_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(mask, n_rows, offsets, idx);
+  { ProfScope ps(K_COMPACT, st); compact_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(mask, n_rows, offsets, idx); }
   CDF_LAUNCH_CHECK("cdf_cache_filter/compact");
   return CDF_OK;
 }

@@ -31,6 +31,20 @@ void set_error(const char* fmt, ...);
     if (e__ != hipSuccess) CDF_FAIL(CDF_ERR_HIP, "%s: %s", name, hipGetErrorString(e__)); \
   } while (0)
 
+// ---- optional per-kernel timing (host side, HIP events on the launch stream) ----
+enum KernelId {
+  K_FILTER = 0, K_SCAN, K_COMPACT, K_QUANTIZE, K_DEQUANTIZE, K_SPMM_PLAN, K_SPMM, K_SPMM_FIXUP,
+  K_GEMM_FWD, K_GEMM_DW, K_GEMM_DW_REDUCE, K_GEMM_DM, K_COUNT
+};
+void prof_begin(int id, hipStream_t st);
+void prof_end(int id, hipStream_t st);
+struct ProfScope {
+  int id;
+  hipStream_t st;
+  ProfScope(int i, hipStream_t s) : id(i), st(s) { prof_begin(id, st); }
+  ~ProfScope() { prof_end(id, st); }
+};
+
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }

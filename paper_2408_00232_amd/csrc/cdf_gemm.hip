@@ -272,6 +272,7 @@ size_t dense_workspace_bytes(int64_t n, int32_t f, int32_t g) {
 template <typename T, int MODE>
 static void launch_gemm(const GemmArgs& a, int Mdim, int Ndim, int slabs, int a_vec, int b_vec, int m_vec,
                         hipStream_t st) {
+  ProfScope ps(MODE == GEMM_FWD ? K_GEMM_FWD : MODE == GEMM_DW ? K_GEMM_DW : K_GEMM_DM, st);
   if (Ndim > 64) {
     dim3 grid(static_cast<unsigned>(ceil_div(Mdim, kBM)), static_cast<unsigned>(ceil_div(Ndim, 128)), slabs);
     gemm_kernel<T, MODE, 128><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
@@ -336,7 +337,10 @@ extern "C" int cdf_dense_bwd(const void* M, int64_t ldm, cdf_dtype dt, const flo
     if (dt == CDF_F32) launch_gemm<float, GEMM_DW>(a, f_in, f_out, slabs, av, bv, mv, st);
     else launch_gemm<bf16_t, GEMM_DW>(a, f_in, f_out, slabs, av, bv, mv, st);
     CDF_LAUNCH_CHECK("cdf_dense_bwd/dW");
-    reduce_slabs_kernel<<<static_cast<unsigned>(ceil_div(count, 256)), 256, 0, st>>>(part, slabs, count, dW);
+    {
+      ProfScope ps(K_GEMM_DW_REDUCE, st);
+      reduce_slabs_kernel<<<static_cast<unsigned>(ceil_div(count, 256)), 256, 0, st>>>(part, slabs, count, dW);
+    }
     CDF_LAUNCH_CHECK("cdf_dense_bwd/reduce");
   }
   // dM = dZ W^T

@@ -22,11 +22,94 @@ void set_error(const char* fmt, ...) {
 
 static size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
 
+// ---- per-kernel timing: one (start, stop) event pair per launch, kept in launch order ----
+static const char* const kKernelNames[K_COUNT] = {
+    "filter_kernel", "scan_kernel", "compact_kernel", "quantize_kernel", "dequantize_kernel",
+    "chunk_rows_kernel", "spmm_kernel", "spmm_fixup_kernel", "gemm_kernel<FWD>", "gemm_kernel<DW>",
+    "reduce_slabs_kernel", "gemm_kernel<DM>"};
+constexpr int kProfCap = 8192;
+struct ProfRec {
+  int id;
+  hipEvent_t a, b;
+};
+static bool g_prof_on = false;
+static ProfRec g_prof[kProfCap];
+static int g_prof_n = 0;      // records in use
+static int g_prof_made = 0;   // records whose events exist (reused across sessions)
+
+void prof_begin(int id, hipStream_t st) {
+  if (!g_prof_on || g_prof_n >= kProfCap) return;
+  ProfRec& r = g_prof[g_prof_n];
+  if (g_prof_n >= g_prof_made) {
+    if (hipEventCreate(&r.a) != hipSuccess || hipEventCreate(&r.b) != hipSuccess) {
+      g_prof_on = false;
+      return;
+    }
+    g_prof_made = g_prof_n + 1;
+  }
+  r.id = id;
+  hipEventRecord(r.a, st);
+}
+
+void prof_end(int id, hipStream_t st) {
+  if (!g_prof_on || g_prof_n >= kProfCap) return;
+  ProfRec& r = g_prof[g_prof_n];
+  if (r.id != id) return;
+  hipEventRecord(r.b, st);
+  ++g_prof_n;
+}
+
 }  // namespace cdf
 
 using namespace cdf;
 
 extern "C" const char* cdf_last_error(void) { return g_err; }
+
+extern "C" int cdf_profile_enable(int on) {
+  g_prof_on = on != 0;
+  if (on) g_prof_n = 0;
+  return CDF_OK;
+}
+
+__global__ __launch_bounds__(256) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
+  for (size_t i = blockIdx.x * static_cast<size_t>(blockDim.x) + threadIdx.x; i < n;
+       i += static_cast<size_t>(gridDim.x) * blockDim.x)
+    dst[i] = src[i];
+}
+
+extern "C" int cdf_profile_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  CDF_REQUIRE(dst && src && bytes % 16 == 0 && aligned(dst, 16) && aligned(src, 16),
+              "cdf_profile_copy: pointers and size must be multiples of 16 bytes");
+  if (bytes == 0) return CDF_OK;
+  const size_t n = bytes / 16;
+  const size_t blocks = (n + 255) / 256;
+  copy_kernel<<<static_cast<unsigned>(blocks < 16384 ? blocks : 16384), 256, 0, static_cast<hipStream_t>(stream)>>>(
+      static_cast<uint4*>(dst), static_cast<const uint4*>(src), n);
+  CDF_LAUNCH_CHECK("cdf_profile_copy");
+  return CDF_OK;
+}
+
+extern "C" int cdf_profile_kernels(void) { return K_COUNT; }
+
+extern "C" const char* cdf_profile_kernel_name(int kernel) {
+  return kernel >= 0 && kernel < K_COUNT ? kKernelNames[kernel] : "";
+}
+
+extern "C" int cdf_profile_read(int kernel, float* ms, int cap) {
+  int n = 0;
+  for (int i = 0; i < g_prof_n; ++i) {
+    if (g_prof[i].id != kernel) continue;
+    if (n < cap && ms) {
+      if (hipEventSynchronize(g_prof[i].b) != hipSuccess) CDF_FAIL(CDF_ERR_HIP, "cdf_profile_read: event sync failed");
+      float t = 0.0f;
+      if (hipEventElapsedTime(&t, g_prof[i].a, g_prof[i].b) != hipSuccess)
+        CDF_FAIL(CDF_ERR_HIP, "cdf_profile_read: elapsed time failed");
+      ms[n] = t;
+    }
+    ++n;
+  }
+  return n;
+}
 
 extern "C" size_t cdf_workspace_bytes(int64_t max_rows, int32_t max_dim, int64_t max_nnz) {
   if (max_rows < 0 || max_dim <= 0 || max_nnz < 0) return 0;

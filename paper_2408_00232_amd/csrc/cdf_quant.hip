@@ -291,8 +291,10 @@ extern "C" int cdf_quantize(const void* cur, void* cached, const int32_t* idx, c
                  idx, n_sent, dim, ld, s.glog, (int)commit, delta ? 1 : 0, codes, meta)
 #define ARGS_BF16 <<<nblocks, kQuantThreads, 0, st>>>(static_cast<const bf16_t*>(cur), static_cast<bf16_t*>(cached), \
                  idx, n_sent, dim, ld, s.glog, (int)commit, delta ? 1 : 0, codes, meta)
+  prof_begin(K_QUANTIZE, st);
   if (dt == CDF_F32) { CDF_DISPATCH_Q(quantize_kernel, float, bits, qs, s.epv, s.nit, ARGS_F32) }
   else { CDF_DISPATCH_Q(quantize_kernel, bf16_t, bits, qs, s.epv, s.nit, ARGS_BF16) }
+  prof_end(K_QUANTIZE, st);
 #undef ARGS_F32
 #undef ARGS_BF16
   CDF_LAUNCH_CHECK("cdf_quantize");
@@ -321,8 +323,10 @@ extern "C" int cdf_dequantize(const uint8_t* codes, const float* meta, const int
                  ld, accumulate ? 1 : 0)
 #define ARGS_BF16 <<<nblocks, kQuantThreads, 0, st>>>(codes, meta, idx, n_sent, dim, s.glog, static_cast<bf16_t*>(dst), \
                  ld, accumulate ? 1 : 0)
+  prof_begin(K_DEQUANTIZE, st);
   if (dt == CDF_F32) { CDF_DISPATCH_Q(dequantize_kernel, float, bits, qs, s.epv, s.nit, ARGS_F32) }
   else { CDF_DISPATCH_Q(dequantize_kernel, bf16_t, bits, qs, s.epv, s.nit, ARGS_BF16) }
+  prof_end(K_DEQUANTIZE, st);
 #undef ARGS_F32
 #undef ARGS_BF16
   CDF_LAUNCH_CHECK("cdf_dequantize");

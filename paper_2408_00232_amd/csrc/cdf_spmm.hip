@@ -40,10 +40,15 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
     int* __restrict__ tail_row) {
   constexpr int U = (8 / NP) > 0 ? (8 / NP) : 1;  // feature rows in flight per wavefront
   const int lane = threadIdx.x & 63;
-  const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + (threadIdx.x >> 6);
+  // the wavefront index is the same in all lanes: say so, and everything derived from it
+  // (chunk bounds, row cursor, loop counters) lives in scalar registers
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + wave;
   if (chunk >= nchunks) return;
   const int64_t s = chunk * kChunk;
   const int L = static_cast<int>(nnz - s < kChunk ? nnz - s : kChunk);
+  int my_col = 0, krel = 0;
+  float my_val = 0.0f;
 
   int r = chunk == 0 ? 0 : chunk_row[chunk];
   bool head = chunk > 0 && rowptr[r] < s;
@@ -108,44 +113,49 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
     clear_acc();
   };
 
-  int krel = 0;
+  // one entry: gather is already in x, add it to the open row (closing rows that ended before it)
+  auto consume = [&](const float (&xr)[NP][EPV], int j) {
+    while (krel == cur_end) {
+      flush_row();
+      next_row();
+    }
+    const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_val), j));
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+      if (col_on[p]) {
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) acc[p][c] = __fmaf_rn(v, xr[p][c], acc[p][c]);
+      }
+    ++krel;
+  };
+  auto gather = [&](float (&xr)[NP][EPV], int j) {
+    const int c = __builtin_amdgcn_readlane(my_col, j);
+    const T* px = X + static_cast<int64_t>(c) * ldx;
+#pragma unroll
+    for (int p = 0; p < NP; ++p)
+      if (col_on[p]) VecIO<T, EPV>::load(px + (p * 64 + lane) * EPV, xr[p]);
+  };
+
   for (int base = 0; base < L; base += 64) {
     const int cnt = L - base < 64 ? L - base : 64;
-    int my_col = 0;
-    float my_val = 0.0f;
+    my_col = 0;
+    my_val = 0.0f;
     if (lane < cnt) {
       my_col = colidx[s + base + lane];
       my_val = vals[s + base + lane];
     }
-    for (int j = 0; j < cnt; j += U) {
+    int j = 0;
+    for (; j + U <= cnt; j += U) {  // U gathers in flight, no guards
       float x[U][NP][EPV];
 #pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (j + u < cnt) {
-          const int c = __builtin_amdgcn_readlane(my_col, j + u);
-          const T* px = X + static_cast<int64_t>(c) * ldx;
+      for (int u = 0; u < U; ++u) gather(x[u], j + u);
 #pragma unroll
-          for (int p = 0; p < NP; ++p)
-            if (col_on[p]) VecIO<T, EPV>::load(px + (p * 64 + lane) * EPV, x[u][p]);
-        }
-      }
-#pragma unroll
-      for (int u = 0; u < U; ++u) {
-        if (j + u < cnt) {
-          while (krel == cur_end) {
-            flush_row();
-            next_row();
-          }
-          const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(my_val), j + u));
-#pragma unroll
-          for (int p = 0; p < NP; ++p)
-            if (col_on[p]) {
-#pragma unroll
-              for (int c = 0; c < EPV; ++c) acc[p][c] = __fmaf_rn(v, x[u][p][c], acc[p][c]);
-            }
-          ++krel;
-        }
-      }
+      for (int u = 0; u < U; ++u) consume(x[u], j + u);
+    }
+    for (; j < cnt; ++j) {
+      float x[NP][EPV];
+      gather(x, j);
+      consume(x, j);
     }
   }
 
@@ -227,7 +237,10 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, int64_t 
   w += align_up(static_cast<size_t>(nc) * dim * sizeof(float), 256);
   float* ptail = reinterpret_cast<float*>(w);
 
-  chunk_rows_kernel<<<static_cast<unsigned>(ceil_div(A->n_rows, 256)), 256, 0, st>>>(A->rowptr, A->n_rows, chunk_row);
+  {
+    ProfScope ps(K_SPMM_PLAN, st);
+    chunk_rows_kernel<<<static_cast<unsigned>(ceil_div(A->n_rows, 256)), 256, 0, st>>>(A->rowptr, A->n_rows, chunk_row);
+  }
   CDF_LAUNCH_CHECK("cdf_spmm/chunk_rows");
   const unsigned nblocks = static_cast<unsigned>(ceil_div(nc, kSpmmWaves));
   const int per_pass = 64 * EPV;
@@ -235,14 +248,19 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, int64_t 
 #define CDF_SPMM_ARGS                                                                                      \
   <<<nblocks, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, ldy, dim, \
                                      chunk_row, nc, phead, ptail, tail_row)
+  prof_begin(K_SPMM, st);
   if (np <= 1) spmm_kernel<T, EPV, 1> CDF_SPMM_ARGS;
   else if (np <= 2) spmm_kernel<T, EPV, 2> CDF_SPMM_ARGS;
   else if (np <= 4) spmm_kernel<T, EPV, 4> CDF_SPMM_ARGS;
   else spmm_kernel<T, EPV, 8> CDF_SPMM_ARGS;
 #undef CDF_SPMM_ARGS
+  prof_end(K_SPMM, st);
   CDF_LAUNCH_CHECK("cdf_spmm/main");
-  spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, ldy, dim,
-                                                               A->n_rows);
+  {
+    ProfScope ps(K_SPMM_FIXUP, st);
+    spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, ldy, dim,
+                                                                 A->n_rows);
+  }
   CDF_LAUNCH_CHECK("cdf_spmm/fixup");
   return CDF_OK;
 }

@@ -1,0 +1,63 @@
+"""Wires a seeded workload (graph partition + dense inputs) into device buffers and C
+argument blocks, and steps the whole model through the library: forward over all layers,
+then backward over all layers, every layer as a generic one (halo gradients included).
+Marshalling only - all arithmetic happens inside libcdf."""
+import torch
+
+from cdfgen import bench_inputs, configs
+
+from . import binding as B
+from .layer import DeviceCsr, LayerBuffers
+
+_TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
+_QS = {"minmax": B.Q_MINMAX, "symmetric": B.Q_SYMMETRIC, "none": B.Q_NONE}
+_NORM = {"linf": B.NORM_LINF, "l2": B.NORM_L2}
+
+
+class Model:
+    def __init__(self, w: configs.Workload, device="cuda:0", rho=0.37, phi=0.01, partition=None):
+        self.w, self.device = w, device
+        P = partition if partition is not None else configs.build_partition(w, device=device)
+        self.P = P
+        self.n_loc, self.n_halo, self.nnz = P.n_loc, P.n_halo, P.nnz
+        self.A = DeviceCsr(P.n_loc, P.n_loc + P.n_halo, P.rowptr, P.colidx, P.vals, device)
+        self.At = DeviceCsr(P.n_loc + P.n_halo, P.n_loc, P.t_rowptr, P.t_colidx, P.t_vals, device)
+        dt = _TORCH_DT[w.dtype]
+        self.layers, self.inputs, self.fwd, self.bwd = [], [], [], []
+        dims = w.layers()
+        for li, (f_in, f_out) in enumerate(dims):
+            L = LayerBuffers(self.A, self.At, P.n_loc, P.n_halo, f_in, f_out, dtype=dt, bits=w.bits,
+                             qs=_QS[w.qscheme], device=device, need_dx=True, keep_z=False)
+            I = bench_inputs.make_layer_inputs(w.seed, li, P.n_loc, P.n_halo, f_in, f_out, rho, phi, device, dt)
+            L.xfull[:P.n_loc] = I.x_local
+            I.x_local = None
+            L.W.copy_(I.W)
+            L.halo_fresh = None   # the two versions below replace the single input buffer
+            L.dH = None
+            relu = li + 1 < len(dims)
+            fa, ba = [], []
+            for v in range(2):
+                a = L.fwd_args(w.eps, _NORM[w.norm], B.COMMIT_CUR, True, relu)
+                a.halo_fresh = I.fresh[v].data_ptr()
+                fa.append(a)
+                b = L.bwd_args(w.eps, _NORM[w.norm], B.COMMIT_CUR, True, relu)
+                b.dH = I.dH[v].data_ptr()
+                ba.append(b)
+            self.layers.append(L)
+            self.inputs.append(I)
+            self.fwd.append(fa)
+            self.bwd.append(ba)
+        rows = max(P.n_loc + P.n_halo, 1)
+        nbytes = B.cdf_workspace_bytes(rows, max(max(d) for d in dims), max(P.nnz, 1))
+        self.ws = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+
+    def step(self, t: int) -> None:
+        """One pass of the hot path: all layers forward, then all layers backward."""
+        v = t & 1
+        for li in range(len(self.layers)):
+            B.cdf_gcn_layer_fwd(self.fwd[li][v], self.ws)
+        for li in reversed(range(len(self.layers))):
+            B.cdf_gcn_layer_bwd(self.bwd[li][v], self.ws)
+
+    def edges_per_step(self) -> int:
+        return self.nnz * len(self.layers)
