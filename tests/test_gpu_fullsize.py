@@ -1,0 +1,193 @@
+"""Parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The model is built exactly as bench.py builds it and stepped twice (zero caches, then the
+stationary state). The oracle cannot redo millions of rows, so it recomputes sampled
+outputs one by one, from the seeded inputs only: the cache/quantiser chain of a halo row
+depends on that row alone, an aggregated row on its neighbours' rows, a dense row on its
+own row. Whole-array properties (ordering and counting of the index list) are checked on
+the device. The backward step is called on seeded stand-ins for the forward results, so
+that none of the oracle's inputs comes from the GPU path.
+"""
+import numpy as np
+import pytest
+import torch
+
+from cdfgen import configs
+from helpers import assert_rows_close, bf16_to_f32
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def host(t):
+    t = t.detach().cpu()
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).numpy().view(np.uint16).copy()
+    return t.numpy().copy()
+
+
+def f64(a):
+    return bf16_to_f32(a).astype(np.float64) if a.dtype == np.uint16 else a.astype(np.float64)
+
+
+def oracle_halo_chain(orc, fa, fb, w, qs, norm):
+    """Two steps of test -> message -> commit -> recover on a set of halo rows (rows are independent)."""
+    sent = np.zeros_like(fa)
+    x = np.zeros_like(fa)
+    out = None
+    for cur in (fa, fb):
+        mask, idx = orc.cache_filter(cur, sent, w.eps, norm)
+        codes, meta = orc.quantize(cur, sent, idx, w.bits, qs, orc.COMMIT_CUR, True)
+        orc.dequantize(codes, meta, idx, x, w.bits, qs, True)
+        out = (mask, idx, codes, meta)
+    return x, sent, out
+
+
+def sample_rows(rowptr, n_rows, n_random, n_longest, seed, max_entries):
+    """Random rows plus the longest ones, bounded in total entries."""
+    lens = rowptr[1:n_rows + 1] - rowptr[:n_rows]
+    g = torch.Generator(device=rowptr.device).manual_seed(seed)
+    rnd = torch.randint(0, n_rows, (n_random,), device=rowptr.device, generator=g)
+    top = torch.topk(lens, min(n_longest, n_rows)).indices
+    rows = torch.unique(torch.cat([rnd, top]))
+    # drop the longest extras if the sample would touch too many entries
+    order = torch.argsort(lens[rows])
+    rows = rows[order]
+    keep = torch.cumsum(lens[rows], 0) <= max_entries
+    keep[-1] = True                         # always keep the longest row
+    return torch.sort(rows[keep]).values
+
+
+def gather_csr_rows(rowptr, colidx, vals, rows):
+    lens = rowptr[rows + 1] - rowptr[rows]
+    ptr = torch.zeros(rows.numel() + 1, dtype=torch.int64, device=rows.device)
+    torch.cumsum(lens, 0, out=ptr[1:])
+    seg = torch.repeat_interleave(torch.arange(rows.numel(), device=rows.device), lens)
+    pos = torch.arange(int(ptr[-1]), device=rows.device) - ptr[seg] + rowptr[rows][seg]
+    return ptr, colidx[pos].long(), vals[pos]
+
+
+@pytest.mark.parametrize("name", ["share", "wide", "large"])
+def test_full_size_sampled(oracle, name):
+    import paper_2408_00232_amd as cdf
+    from paper_2408_00232_amd.workload import Model
+    orc = oracle
+    w = configs.ALL[name]
+    model = Model(w, DEV)
+    P = model.P
+    n, h = P.n_loc, P.n_halo
+    qs = {"minmax": orc.Q_MINMAX, "symmetric": orc.Q_SYMMETRIC, "none": orc.Q_NONE}[w.qscheme]
+    norm = {"linf": orc.NORM_LINF, "l2": orc.NORM_L2}[w.norm]
+    model.step(0)
+    model.step(1)
+    torch.cuda.synchronize()
+    nl = len(model.layers)
+    for li in range(nl):
+        L, I = model.layers[li], model.inputs[li]
+        f_in, f_out = L.f_in, L.f_out
+        relu = li + 1 < nl
+        # ---- whole-array properties of the forward index list (on the device) ----
+        ns = int(L.n_sent.item())
+        mask = L.mask[:h]
+        assert ns == int(mask.sum().item())
+        assert torch.equal(L.idx[:ns].long(), torch.nonzero(mask).flatten())
+        assert torch.equal(mask.bool(), I.sent_set), "exactly the drifting rows fail the test"
+        # ---- sampled halo rows: mask, codes, meta, committed cache, recovered rows ----
+        g = torch.Generator(device=DEV).manual_seed(100 + li)
+        S = torch.unique(torch.randint(0, h, (4096,), device=DEV, generator=g))
+        fa, fb = host(I.fresh[0][S]), host(I.fresh[1][S])
+        ox, osent, (omask, oidx, ocodes, ometa) = oracle_halo_chain(orc, fa, fb, w, qs, norm)
+        np.testing.assert_array_equal(host(mask[S]), omask)
+        np.testing.assert_array_equal(host(L.cache_sent[S]), osent)
+        np.testing.assert_array_equal(host(L.xfull[n:][S]), ox)
+        sent_rows = S[torch.from_numpy(oidx).long().to(DEV)]
+        k = torch.searchsorted(L.idx[:ns].long(), sent_rows)          # position of each message
+        assert torch.equal(L.idx[:ns].long()[k], sent_rows)
+        rb = L.row_bytes
+        gcodes = L.codes[: ns * rb].view(ns, rb)[k]
+        np.testing.assert_array_equal(host(gcodes), ocodes)
+        np.testing.assert_array_equal(host(L.meta[:ns][k]), ometa)
+        # ---- sampled aggregated rows and their dense transform ----
+        rows = sample_rows(P.rowptr, n, 192, 8, 200 + li, 3_000_000)
+        ptr, cols, vals = gather_csr_rows(P.rowptr, P.colidx, P.vals, rows)
+        touched, inv = torch.unique(cols, return_inverse=True)
+        is_halo = touched >= n
+        xt = np.zeros((touched.numel(), f_in), host(L.xfull[:1]).dtype)
+        xt[host(~is_halo).astype(bool)] = host(L.xfull[touched[~is_halo]])       # local rows are inputs
+        th = touched[is_halo] - n
+        oxh, _, _ = oracle_halo_chain(orc, host(I.fresh[0][th]), host(I.fresh[1][th]), w, qs, norm)
+        xt[host(is_halo).astype(bool)] = oxh
+        oM = orc.spmm(host(ptr), host(inv.to(torch.int32)), host(vals), touched.numel(), xt)
+        gM = host(L.M[rows])
+        if w.dtype == "f32":
+            assert_rows_close(gM, oM, what=f"layer {li} M")
+        else:
+            gm, om = f64(gM), f64(oM)
+            rowmax = np.maximum(np.abs(om).max(1, keepdims=True), 1e-30)
+            assert (np.abs(gm - om) <= np.abs(om) * 2.0 ** -7 + 1e-4 * rowmax).all()
+        # dense rows from the oracle's own M rows (bf16: the two M differ by rounding steps)
+        oZ, oH = orc.dense_fwd(oM, host(L.W), relu)
+        assert_rows_close(host(L.H[rows]), oH, rel=1e-4 if w.dtype == "f32" else 2e-2,
+                          frob=1e-5 if w.dtype == "f32" else 1e-2, what=f"layer {li} H")
+
+    # ---- backward at full size on seeded stand-ins for M and H ----
+    for li in range(nl):
+        L, I = model.layers[li], model.inputs[li]
+        f_in, f_out = L.f_in, L.f_out
+        relu = li + 1 < nl
+        g = torch.Generator(device=DEV).manual_seed(300 + li)
+        L.M.copy_(torch.randn(n, f_in, device=DEV, generator=g).to(L.M.dtype))
+        L.H.copy_(torch.randn(n, f_out, device=DEV, generator=g))
+        L.gcache_sent.zero_()
+        cdf.cdf_gcn_layer_bwd(model.bwd[li][0], model.ws)
+        torch.cuda.synchronize()
+        dH = I.dH[0]
+        W = host(L.W)
+        # dW entries: full-length dot products of one column of M with one masked column of dH
+        rs = np.random.default_rng(400 + li)
+        gdW = host(L.dW)
+        colscale = np.abs(gdW).max()
+        for _ in range(6):
+            i, j = int(rs.integers(f_in)), int(rs.integers(f_out))
+            mcol = f64(host(L.M[:, i].contiguous().view(-1, 1))).ravel()
+            dz = host(dH[:, j]).astype(np.float64)
+            if relu:
+                dz = dz * (host(L.H[:, j]) > 0)
+            want = float(mcol @ dz)
+            assert abs(float(gdW[i, j]) - want) <= 1e-4 * colscale
+        # dM rows and dxfull rows (local and halo) from the rows they depend on
+        trows = sample_rows(P.t_rowptr, n + h, 192, 8, 500 + li, 2_000_000)
+        ptr, cols, vals = gather_csr_rows(P.t_rowptr, P.t_colidx, P.t_vals, trows)
+        touched, inv = torch.unique(cols, return_inverse=True)
+        Mt, Ht, dHt = host(L.M[touched]), host(L.H[touched]), host(dH[touched])
+        _, odM = orc.dense_bwd(Mt, W, Ht, dHt, relu)
+        gdM = host(L.dM[touched])
+        odx = orc.spmm(host(ptr), host(inv.to(torch.int32)), host(vals), touched.numel(), odM)
+        gdx = host(L.dxfull[trows])
+        if w.dtype == "f32":
+            assert_rows_close(gdM, odM, what=f"layer {li} dM")
+            assert_rows_close(gdx, odx, what=f"layer {li} dxfull")
+        else:
+            for gg, oo in ((gdM, odM), (gdx, odx)):
+                a, b = f64(gg), f64(oo)
+                rowmax = np.maximum(np.abs(b).max(1, keepdims=True), 1e-30)
+                assert (np.abs(a - b) <= np.abs(b) * 2.0 ** -6 + 2e-3 * rowmax).all()
+        # gradient messages from a zero cache: every non-zero halo row is sent, in order
+        gn = int(L.gn_sent.item())
+        nzrow = (L.dxfull[n:] != 0).any(1)
+        assert gn == int(nzrow.sum().item())
+        assert torch.equal(L.gidx[:gn].long(), torch.nonzero(nzrow).flatten())
+        assert torch.equal(L.gcache_sent, L.dxfull[n:] * nzrow.view(-1, 1).to(L.dxfull.dtype))
+    del model
+    torch.cuda.empty_cache()
+
+
+def test_full_size_mid_all_rows(oracle):
+    """The mid workload is small enough for the oracle to redo every row of both layers."""
+    import paper_2408_00232_amd as cdf
+    from test_gpu_parity import layer_case
+    w = configs.MID
+    P = configs.build_partition(w)
+    for eps in (0.0, 0.01, 0.1):
+        layer_case(cdf, oracle, P, 602, 256, eps, 0, 8, 0, 1, True, True, epochs=2)
+    layer_case(cdf, oracle, P, 256, 41, 0.1, 0, 8, 0, 1, True, False, epochs=2)
