@@ -32,7 +32,7 @@ def spmm_bytes(rows_out, rows_in, nnz, dim, esz):
     return csr + out + rows_in * dim * esz, csr + out + nnz * dim * esz
 
 
-def cpu_baseline(model, budget_edges=4_000_000):
+def cpu_baseline(model, budget_edges=12_000_000):
     """The oracle, as it stands, on a bounded sample of the same workload: every k-th local row of
     the partition (with all columns those rows touch), one stationary step of all layers."""
     import numpy as np
@@ -206,6 +206,45 @@ def main():
                     f_b, w_b = line.split("=")[1].split()
                     roof["traffic"] = float(f_b) + float(w_b)
 
+    # every HBM-bound kernel against its own algorithmic bytes, every dense kernel against the fp32
+    # matrix-core peak (per-launch averages over the timed region; widths differ between layers)
+    def avg(xs):
+        return sum(xs) / len(xs)
+    lay = w.layers()
+    sent_f = [int(L.n_sent.item()) for L in model.layers]
+    sent_b = [int(L.gn_sent.item()) for L in model.layers]
+    rb = [L.row_bytes for L in model.layers]
+    alg = {
+        "filter_kernel": avg([h * (2 * f * esz + 1) + 4 * sent_f[i] for i, (f, _) in enumerate(lay)] +
+                             [h * (2 * f * esz + 1) + 4 * sent_b[i] for i, (f, _) in enumerate(lay)]),
+        "quantize_kernel": avg([sent_f[i] * (3 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)] +
+                               [sent_b[i] * (3 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)]),
+        "dequantize_kernel": avg([sent_f[i] * (2 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)]),
+    }
+    flops = avg([2.0 * n * f * g for f, g in lay])
+    per_kernel = {}
+    for name, b in alg.items():
+        if name in kernels:
+            gbs = b / (kernels[name]["avg_ms"] * 1e-3) / 1e9
+            per_kernel[name] = {"bound": "hbm", "algorithmic_bytes_per_launch": b, "achieved_GBps": gbs,
+                                "frac": gbs / HBM_PEAK_GBS}
+    for name in ("gemm_kernel<FWD>", "gemm_kernel<DW>", "gemm_kernel<DM>"):
+        if name in kernels:
+            tf = flops / (kernels[name]["avg_ms"] * 1e-3) / 1e12
+            per_kernel[name] = {"bound": "mfma", "flops_per_launch": flops, "achieved_TFLOPs": tf,
+                                "frac": tf / 157.3}
+    # measured streaming ceiling: the library's plain copy kernel on 1 GiB (read + write bytes)
+    src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+    dst = torch.zeros_like(src)
+    cdf.cdf_profile_copy(dst, src)
+    torch.cuda.synchronize()
+    tc = time.perf_counter()
+    for _ in range(10):
+        cdf.cdf_profile_copy(dst, src)
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2 * (1 << 30) / (time.perf_counter() - tc) / 1e9
+    del src, dst
+
     rho_f = [int(L.n_sent.item()) / max(h, 1) for L in model.layers]
     rho_b = [int(L.gn_sent.item()) / max(h, 1) for L in model.layers]
 
@@ -222,6 +261,8 @@ def main():
                    "send_fraction_bwd": rho_b},
         "roofline": roof,
         "kernels": kernels,
+        "kernel_rooflines": per_kernel,
+        "copy_ceiling_GBps": copy_gbs,
     }
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a sample ...")

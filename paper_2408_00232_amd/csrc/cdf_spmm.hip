@@ -1,7 +1,7 @@
 // CSR aggregation Y = A X over the normalised adjacency (Sec. 3.1) and its transposed
 // counterpart for back-propagation (the same kernel on the CSR of A^T).
 //
-// Work split: the stored entries are cut into chunks of kChunk consecutive entries and
+// Work split: the stored entries are cut into chunks of 256 to 1024 consecutive entries and
 // each wavefront takes one chunk, whatever rows it covers - a power-law degree
 // distribution (rows of 1 to several 10^5 entries) therefore loads every wavefront
 // equally. Inside a chunk the wavefront walks the entries in storage order: the 64
@@ -20,12 +20,13 @@
 
 namespace cdf {
 
-constexpr int kChunk = 256;        // stored entries per wavefront
+constexpr int kChunk = 256;        // stored entries per wavefront (smallest; sizes the workspace)
 constexpr int kSpmmThreads = 256;  // 4 wavefronts per block
 constexpr int kSpmmWaves = kSpmmThreads / 64;
 
-// chunk_row[c] = row that holds stored entry c*kChunk (c >= 1; entry 0 is handled as row 0).
-__global__ void chunk_rows_kernel(const int64_t* __restrict__ rowptr, int n_rows, int* __restrict__ chunk_row) {
+// chunk_row[c] = row that holds stored entry c*chunk (c >= 1; entry 0 is handled as row 0).
+__global__ void chunk_rows_kernel(const int64_t* __restrict__ rowptr, int n_rows, int* __restrict__ chunk_row,
+                                  int kChunk) {
   const int r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r >= n_rows) return;
   const int64_t a = rowptr[r], b = rowptr[r + 1];
@@ -37,7 +38,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
     const int64_t* __restrict__ rowptr, const int* __restrict__ colidx, const float* __restrict__ vals,
     int n_rows, int64_t nnz, const T* __restrict__ X, int64_t ldx, T* __restrict__ Y, int64_t ldy, int dim,
     const int* __restrict__ chunk_row, int64_t nchunks, float* __restrict__ phead, float* __restrict__ ptail,
-    int* __restrict__ tail_row) {
+    int* __restrict__ tail_row, int kChunk) {
   constexpr int U = (8 / NP) > 0 ? (8 / NP) : 1;  // feature rows in flight per wavefront
   const int lane = threadIdx.x & 63;
   // the wavefront index is the same in all lanes: say so, and everything derived from it
@@ -225,10 +226,19 @@ size_t spmm_workspace_bytes(int64_t nnz, int32_t dim) {
          2 * align_up(static_cast<size_t>(nc) * dim * sizeof(float), 256);
 }
 
+// Entries per wavefront: 256 for small matrices (enough wavefronts to fill 256 CUs), up to 1024
+// for large ones (fewer straddling-row pieces). Always a multiple of 64 and >= kChunk.
+static int pick_chunk(int64_t nnz) {
+  int c = kChunk;
+  while (c < 1024 && nnz / (2 * c) >= 65536) c *= 2;
+  return c;
+}
+
 template <typename T, int EPV>
 static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, int64_t ldy, int dim, void* ws,
                        hipStream_t st) {
-  const int64_t nc = spmm_chunks(A->nnz);
+  const int chunk = pick_chunk(A->nnz);
+  const int64_t nc = A->nnz <= 0 ? 1 : ceil_div(A->nnz, chunk);
   char* w = static_cast<char*>(ws);
   int* chunk_row = reinterpret_cast<int*>(w);
   int* tail_row = chunk_row + nc;
@@ -239,7 +249,8 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, int64_t 
 
   {
     ProfScope ps(K_SPMM_PLAN, st);
-    chunk_rows_kernel<<<static_cast<unsigned>(ceil_div(A->n_rows, 256)), 256, 0, st>>>(A->rowptr, A->n_rows, chunk_row);
+    chunk_rows_kernel<<<static_cast<unsigned>(ceil_div(A->n_rows, 256)), 256, 0, st>>>(A->rowptr, A->n_rows, chunk_row,
+                                                                                       chunk);
   }
   CDF_LAUNCH_CHECK("cdf_spmm/chunk_rows");
   const unsigned nblocks = static_cast<unsigned>(ceil_div(nc, kSpmmWaves));
@@ -247,7 +258,7 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, int64_t 
   const int np = static_cast<int>(ceil_div(dim, per_pass));
 #define CDF_SPMM_ARGS                                                                                      \
   <<<nblocks, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, ldy, dim, \
-                                     chunk_row, nc, phead, ptail, tail_row)
+                                     chunk_row, nc, phead, ptail, tail_row, chunk)
   prof_begin(K_SPMM, st);
   if (np <= 1) spmm_kernel<T, EPV, 1> CDF_SPMM_ARGS;
   else if (np <= 2) spmm_kernel<T, EPV, 2> CDF_SPMM_ARGS;
