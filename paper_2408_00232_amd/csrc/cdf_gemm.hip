@@ -57,7 +57,12 @@ __device__ __forceinline__ void load_quad(const T* p, int at, int len, bool vec_
   }
 }
 
-template <typename T, int MODE, int BN>
+// FAST: every tile is full (no bounds checks) and every operand row is 16-byte aligned
+// (no scalar fall-back); decided on the host.
+template <typename T>
+__device__ __forceinline__ void load_quad_fast(const T* p, float (&v)[4]) { VecIO<T, 4>::load(p, v); }
+
+template <typename T, int MODE, int BN, bool FAST>
 __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_vec, int b_vec, int m_vec) {
   constexpr int SB = BN + 4;
   constexpr int TN = BN / 64;   // 32-wide MFMA tiles per wavefront along n (waves are 2 x 2)
@@ -93,7 +98,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_ve
       for (int i = 0; i < 4; ++i) {
         const int m = m0 + (tid >> 3) + 32 * i;
         const int k = k0 + (tid & 7) * 4;
-        if (m < Mdim && k < Kend) load_quad<T>(Ap + static_cast<int64_t>(m) * a.lda + k, k, Kend, a_vec, ra[i]);
+        if (FAST) load_quad_fast<T>(Ap + static_cast<int64_t>(m) * a.lda + k, ra[i]);
+        else if (m < Mdim && k < Kend) load_quad<T>(Ap + static_cast<int64_t>(m) * a.lda + k, k, Kend, a_vec, ra[i]);
         else ra[i][0] = ra[i][1] = ra[i][2] = ra[i][3] = 0.0f;
       }
     } else if (MODE == GEMM_DM) {
@@ -102,12 +108,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_ve
       for (int i = 0; i < 4; ++i) {
         const int m = m0 + (tid >> 3) + 32 * i;
         const int k = k0 + (tid & 7) * 4;
-        if (m < Mdim && k < Kend) {
+        if (FAST || (m < Mdim && k < Kend)) {
           const int64_t off = static_cast<int64_t>(m) * a.g + k;
-          load_quad<float>(dHp + off, k, Kend, a_vec, ra[i]);
+          if (FAST) load_quad_fast<float>(dHp + off, ra[i]);
+          else load_quad<float>(dHp + off, k, Kend, a_vec, ra[i]);
           if (a.relu) {
             float z[4];
-            load_quad<float>(a.mask + off, k, Kend, m_vec, z);
+            if (FAST) load_quad_fast<float>(a.mask + off, z);
+            else load_quad<float>(a.mask + off, k, Kend, m_vec, z);
 #pragma unroll
             for (int c = 0; c < 4; ++c) ra[i][c] = z[c] > 0.0f ? ra[i][c] : 0.0f;
           }
@@ -119,7 +127,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_ve
       for (int i = 0; i < 4; ++i) {
         const int k = k0 + (tid >> 5) + 8 * i;
         const int m = m0 + (tid & 31) * 4;
-        if (k < Kend && m < Mdim) load_quad<T>(Ap + static_cast<int64_t>(k) * a.lda + m, m, Mdim, a_vec, ra[i]);
+        if (FAST) load_quad_fast<T>(Ap + static_cast<int64_t>(k) * a.lda + m, ra[i]);
+        else if (k < Kend && m < Mdim) load_quad<T>(Ap + static_cast<int64_t>(k) * a.lda + m, m, Mdim, a_vec, ra[i]);
         else ra[i][0] = ra[i][1] = ra[i][2] = ra[i][3] = 0.0f;
       }
     }
@@ -130,7 +139,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_ve
       for (int i = 0; i < BQ; ++i) {
         const int k = k0 + tid / (BN / 4) + (1024 / BN) * i;
         const int n = n0 + (tid % (BN / 4)) * 4;
-        if (k < Kend && n < Ndim) load_quad<float>(a.B + static_cast<int64_t>(k) * a.g + n, n, Ndim, b_vec, rb[i]);
+        if (FAST) load_quad_fast<float>(a.B + static_cast<int64_t>(k) * a.g + n, rb[i]);
+        else if (k < Kend && n < Ndim) load_quad<float>(a.B + static_cast<int64_t>(k) * a.g + n, n, Ndim, b_vec, rb[i]);
         else rb[i][0] = rb[i][1] = rb[i][2] = rb[i][3] = 0.0f;
       }
     } else if (MODE == GEMM_DM) {
@@ -139,7 +149,8 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_ve
       for (int i = 0; i < BQ; ++i) {
         const int n = n0 + (tid >> 3) + 32 * i;
         const int k = k0 + (tid & 7) * 4;
-        if (n < Ndim && k < Kend) load_quad<float>(a.B + static_cast<int64_t>(n) * a.g + k, k, Kend, b_vec, rb[i]);
+        if (FAST) load_quad_fast<float>(a.B + static_cast<int64_t>(n) * a.g + k, rb[i]);
+        else if (n < Ndim && k < Kend) load_quad<float>(a.B + static_cast<int64_t>(n) * a.g + k, k, Kend, b_vec, rb[i]);
         else rb[i][0] = rb[i][1] = rb[i][2] = rb[i][3] = 0.0f;
       }
     } else {
@@ -148,12 +159,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_ve
       for (int i = 0; i < BQ; ++i) {
         const int k = k0 + tid / (BN / 4) + (1024 / BN) * i;
         const int n = n0 + (tid % (BN / 4)) * 4;
-        if (k < Kend && n < Ndim) {
+        if (FAST || (k < Kend && n < Ndim)) {
           const int64_t off = static_cast<int64_t>(k) * a.g + n;
-          load_quad<float>(a.B + off, n, Ndim, b_vec, rb[i]);
+          if (FAST) load_quad_fast<float>(a.B + off, rb[i]);
+          else load_quad<float>(a.B + off, n, Ndim, b_vec, rb[i]);
           if (a.relu) {
             float z[4];
-            load_quad<float>(a.mask + off, n, Ndim, m_vec, z);
+            if (FAST) load_quad_fast<float>(a.mask + off, z);
+            else load_quad<float>(a.mask + off, n, Ndim, m_vec, z);
 #pragma unroll
             for (int c = 0; c < 4; ++c) rb[i][c] = z[c] > 0.0f ? rb[i][c] : 0.0f;
           }
@@ -223,11 +236,11 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_ve
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * (BN / 2) + j * 32 + l32;
-      if (col >= Ndim) continue;
+      if (!FAST && col >= Ndim) continue;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int row = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
-        if (row >= Mdim) continue;
+        if (!FAST && row >= Mdim) continue;
         const float v = acc[i][j][e];
         if (MODE == GEMM_FWD) {
           const int64_t off = static_cast<int64_t>(row) * a.g + col;
@@ -244,13 +257,19 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_ve
     }
 }
 
-// dW[i] = sum over slabs, in slab order
-__global__ void reduce_slabs_kernel(const float* __restrict__ part, int slabs, int64_t count, float* __restrict__ out) {
-  const int64_t i = static_cast<int64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (i >= count) return;
+// dW[i] = sum over slabs in a fixed order: four interleaved running sums (slab k goes to sum
+// k mod 4), combined as (s0 + s1) + (s2 + s3). 64 outputs per block of 256 threads.
+__global__ __launch_bounds__(256) void reduce_slabs_kernel(const float* __restrict__ part, int slabs, int64_t count,
+                                                           float* __restrict__ out) {
+  __shared__ float sh[4][64];
+  const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int64_t i = static_cast<int64_t>(blockIdx.x) * 64 + e;
   float s = 0.0f;
-  for (int k = 0; k < slabs; ++k) s = s + part[k * count + i];
-  out[i] = s;
+  if (i < count)
+    for (int k = g; k < slabs; k += 4) s = s + part[k * count + i];
+  sh[g][e] = s;
+  __syncthreads();
+  if (g == 0 && i < count) out[i] = (sh[0][e] + sh[1][e]) + (sh[2][e] + sh[3][e]);
 }
 
 constexpr size_t kDwPartialCap = size_t(512) << 20;  // bytes of slab partials at most
@@ -258,6 +277,9 @@ constexpr size_t kDwPartialCap = size_t(512) << 20;  // bytes of slab partials a
 static void dw_split(int n, int f, int g, int* slab_rows, int* slabs) {
   int64_t rows = 2048;
   const size_t per = static_cast<size_t>(f) * g * sizeof(float);
+  // enough blocks to fill the chip a few times over (tiles x slabs >= ~1500), not more
+  const int64_t tiles = ceil_div(f, kBM) * ceil_div(g, g > 64 ? 128 : 64);
+  while (ceil_div(n, rows * 2) * tiles >= 1536) rows *= 2;
   while (static_cast<size_t>(ceil_div(n, rows)) * per > kDwPartialCap) rows *= 2;
   *slab_rows = static_cast<int>(rows);
   *slabs = static_cast<int>(ceil_div(n > 0 ? n : 1, rows));
@@ -273,12 +295,18 @@ template <typename T, int MODE>
 static void launch_gemm(const GemmArgs& a, int Mdim, int Ndim, int slabs, int a_vec, int b_vec, int m_vec,
                         hipStream_t st) {
   ProfScope ps(MODE == GEMM_FWD ? K_GEMM_FWD : MODE == GEMM_DW ? K_GEMM_DW : K_GEMM_DM, st);
-  if (Ndim > 64) {
-    dim3 grid(static_cast<unsigned>(ceil_div(Mdim, kBM)), static_cast<unsigned>(ceil_div(Ndim, 128)), slabs);
-    gemm_kernel<T, MODE, 128><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
+  const int bn = Ndim > 64 ? 128 : 64;
+  // reduction length: f_in (FWD), f_out (DM), rows per slab (DW: every slab must be full)
+  const int Kdim = MODE == GEMM_FWD ? a.f : MODE == GEMM_DM ? a.g : a.slab_rows;
+  const bool k_full = Kdim % kBK == 0 && (MODE != GEMM_DW || a.n % a.slab_rows == 0);
+  const bool fast = Mdim % kBM == 0 && Ndim % bn == 0 && k_full && a_vec && b_vec && (!a.relu || MODE == GEMM_FWD || m_vec);
+  dim3 grid(static_cast<unsigned>(ceil_div(Mdim, kBM)), static_cast<unsigned>(ceil_div(Ndim, bn)), slabs);
+  if (bn == 128) {
+    if (fast) gemm_kernel<T, MODE, 128, true><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
+    else gemm_kernel<T, MODE, 128, false><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
   } else {
-    dim3 grid(static_cast<unsigned>(ceil_div(Mdim, kBM)), 1, slabs);
-    gemm_kernel<T, MODE, 64><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
+    if (fast) gemm_kernel<T, MODE, 64, true><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
+    else gemm_kernel<T, MODE, 64, false><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
   }
 }
 
@@ -339,7 +367,7 @@ extern "C" int cdf_dense_bwd(const void* M, int64_t ldm, cdf_dtype dt, const flo
     CDF_LAUNCH_CHECK("cdf_dense_bwd/dW");
     {
       ProfScope ps(K_GEMM_DW_REDUCE, st);
-      reduce_slabs_kernel<<<static_cast<unsigned>(ceil_div(count, 256)), 256, 0, st>>>(part, slabs, count, dW);
+      reduce_slabs_kernel<<<static_cast<unsigned>(ceil_div(count, 64)), 256, 0, st>>>(part, slabs, count, dW);
     }
     CDF_LAUNCH_CHECK("cdf_dense_bwd/reduce");
   }

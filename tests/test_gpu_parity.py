@@ -241,7 +241,7 @@ def test_spmm_long_and_empty_rows(cdf, oracle):
 
 
 DENSE_SHAPES = [(1000, 100, 47), (300, 602, 256), (513, 16, 8), (700, 128, 256), (257, 256, 41), (130, 64, 64),
-                (5000, 128, 16), (64, 33, 130)]
+                (5000, 128, 16), (64, 33, 130), (4096, 128, 256), (2048, 256, 64), (1024, 64, 128)]
 
 
 @pytest.mark.parametrize("n,f,g", DENSE_SHAPES)
