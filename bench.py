@@ -81,10 +81,26 @@ def cpu_baseline(model, budget_edges=12_000_000):
     state = []
     for li, L in enumerate(model.layers):
         I = model.inputs[li]
+        if model.tf[li]:
+            # transform-first layer: the exchanged rows are rows of T = X W. Columns of the sample
+            # that are local rows of the partition get their T row from the oracle's own transform.
+            is_h = other >= P.n_loc
+            Wn = host(L.W)
+            t_loc, _ = oracle.dense_fwd(host(L.x_local[other[~is_h]]), Wn, relu=False)
+            fresh = []
+            for v in range(2):
+                fr = np.zeros((other.numel(), L.f_out), np.float32)
+                fr[host(~is_h)] = t_loc
+                fr[host(is_h)] = host(I.fresh[v][other[is_h] - P.n_loc])
+                fresh.append(fr)
+            state.append(dict(tf=True, x=host(L.x_local[rows]), t=np.zeros((n_s + h_s, L.f_out), np.float32),
+                              fresh=fresh, sent=np.zeros_like(fresh[0]), gsent=np.zeros_like(fresh[0]), W=Wn,
+                              dH=[host(I.dH[v][rows]) for v in range(2)]))
+            continue
         full = [torch.cat([L.xfull[:P.n_loc], I.fresh[v]]) for v in range(2)]
         fresh = [host(f[other]) for f in full]
         x = np.concatenate([host(L.xfull[rows]), np.zeros_like(fresh[0])])
-        state.append(dict(x=x, fresh=fresh, sent=np.zeros_like(fresh[0]), gsent=np.zeros_like(fresh[0]),
+        state.append(dict(tf=False, x=x, fresh=fresh, sent=np.zeros_like(fresh[0]), gsent=np.zeros_like(fresh[0]),
                           W=host(L.W), dH=[host(I.dH[v][rows]) for v in range(2)]))
         del full
     nl = len(model.layers)
@@ -93,10 +109,18 @@ def cpu_baseline(model, budget_edges=12_000_000):
         outs = []
         for li in range(nl):
             s = state[li]
+            if s["tf"]:
+                outs.append(oracle.layer_tf_fwd(A, n_s, h_s, s["x"], s["t"], s["fresh"][v], s["sent"], s["W"], w.eps,
+                                                norm, w.bits, qs, oracle.COMMIT_CUR, li + 1 < nl, True))
+                continue
             outs.append(oracle.layer_fwd(A, n_s, h_s, s["x"], s["fresh"][v], s["sent"], s["W"], w.eps, norm,
                                          w.bits, qs, oracle.COMMIT_CUR, li + 1 < nl, True))
         for li in reversed(range(nl)):
             s = state[li]
+            if s["tf"]:
+                oracle.layer_tf_bwd(At, n_s, h_s, s["x"], outs[li]["H"], s["dH"][v], s["W"], s["gsent"], w.eps, norm,
+                                    w.bits, qs, oracle.COMMIT_CUR, li + 1 < nl, True, True)
+                continue
             oracle.layer_bwd(At, n_s, h_s, outs[li]["M"], outs[li]["H"], s["dH"][v], s["W"], s["gsent"], w.eps,
                              norm, w.bits, qs, oracle.COMMIT_CUR, li + 1 < nl, True, True)
 
@@ -117,6 +141,8 @@ def main():
     ap.add_argument("--workload", default="share", help="tiny | mid | large | wide | share")
     ap.add_argument("--rho", type=float, default=0.37, help="fraction of halo rows refreshed per step")
     ap.add_argument("--phi", type=float, default=0.01, help="fraction of local rows whose gradient changes")
+    ap.add_argument("--order", default="auto", choices=["auto", "aggregate"],
+                    help="auto: layers with f_out < f_in compute A (X W); aggregate: every layer computes (A X) W")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB (for scaling hardware counters)")
@@ -136,7 +162,7 @@ def main():
     w = configs.ALL[args.workload]
     t_setup = time.time()
     log(f"[bench] building workload '{w.name}' on {dev} ...")
-    model = Model(w, dev, rho=args.rho, phi=args.phi)
+    model = Model(w, dev, rho=args.rho, phi=args.phi, order=args.order)
     torch.cuda.synchronize()
     log(f"[bench] partition: n_loc={model.n_loc} n_halo={model.n_halo} nnz={model.nnz} "
         f"layers={w.layers()} setup {time.time() - t_setup:.1f}s "
@@ -181,8 +207,9 @@ def main():
     # then backward layers L-1..0 on A^T; algorithmic bytes differ per launch (feature width).
     esz = 2 if w.dtype == "bf16" else 4
     n, h, nnz = model.n_loc, model.n_halo, model.nnz
-    per_step = [spmm_bytes(n, n + h, nnz, f, esz) for f, _ in w.layers()] + \
-               [spmm_bytes(n + h, n, nnz, f, esz) for f, _ in reversed(w.layers())]
+    widths = model.spmm_widths()
+    per_step = [spmm_bytes(n, n + h, nnz, f, esz) for f in widths] + \
+               [spmm_bytes(n + h, n, nnz, f, esz) for f in reversed(widths)]
     nl = len(per_step)
     roof = None
     if spmm_ms and len(spmm_ms) == nl * args.steps:
@@ -210,7 +237,7 @@ def main():
     # matrix-core peak (per-launch averages over the timed region; widths differ between layers)
     def avg(xs):
         return sum(xs) / len(xs)
-    lay = w.layers()
+    lay = [(f, g) for f, g in zip(widths, [g for _, g in w.layers()])]   # (width of the halo rows, f_out)
     sent_f = [int(L.n_sent.item()) for L in model.layers]
     sent_b = [int(L.gn_sent.item()) for L in model.layers]
     rb = [L.row_bytes for L in model.layers]
@@ -221,7 +248,7 @@ def main():
                                [sent_b[i] * (3 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)]),
         "dequantize_kernel": avg([sent_f[i] * (2 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)]),
     }
-    flops = avg([2.0 * n * f * g for f, g in lay])
+    flops = avg([2.0 * n * f * g for f, g in w.layers()])
     per_kernel = {}
     for name, b in alg.items():
         if name in kernels:
@@ -257,6 +284,7 @@ def main():
                                f"{w.parts} ({w.partitioner}), n_loc={n}, n_halo={h}, nnz={nnz}, layers "
                                f"{'-'.join(str(d) for d in w.dims)}, {w.bits}-bit {w.qscheme} messages, "
                                f"eps={w.eps} ({w.norm})",
+                   "order_per_layer": ["transform-first" if t else "aggregate-first" for t in model.tf],
                    "edges_per_step": model.edges_per_step(), "send_fraction_fwd": rho_f,
                    "send_fraction_bwd": rho_b},
         "roofline": roof,

@@ -31,16 +31,19 @@ def _randn(shape, gen, device, dtype):
 
 
 def make_layer_inputs(seed, layer, n_loc, n_halo, f_in, f_out, rho=0.37, phi=0.01, device="cpu",
-                      dtype=torch.float32) -> LayerInputs:
+                      dtype=torch.float32, halo_width=None) -> LayerInputs:
+    """halo_width: width of the rows that cross the partition boundary (f_in when the layer
+    aggregates first, f_out when it transforms first)."""
+    hw = f_in if halo_width is None else halo_width
     gen = torch.Generator(device=device)
     gen.manual_seed(seed * 1000 + layer)
     x_local = _randn((n_loc, f_in), gen, device, dtype)
-    fa = _randn((n_halo, f_in), gen, device, torch.float32)
+    fa = _randn((n_halo, hw), gen, device, torch.float32)
     u = rng.uniform01(seed, 300 + layer, torch.arange(n_halo, dtype=torch.int64, device=device))
     in_s = u < rho
     # strong change on S (factor 1 + 0.5 g), faint change elsewhere (1 + 0.002 g)
     amp = torch.where(in_s, torch.tensor(0.5, device=device), torch.tensor(0.002, device=device)).view(-1, 1)
-    fb = fa * (1.0 + amp * torch.randn((n_halo, f_in), generator=gen, device=device))
+    fb = fa * (1.0 + amp * torch.randn((n_halo, hw), generator=gen, device=device))
     del amp
     lim = (6.0 / (f_in + f_out)) ** 0.5
     W = (torch.rand((f_in, f_out), generator=gen, device=device) * 2 - 1) * lim

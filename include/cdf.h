@@ -255,6 +255,80 @@ typedef struct {
 
 int cdf_gcn_layer_bwd(const cdf_layer_bwd_args* args /* host */, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Transform-first variant of the layer step: Z = A^ (X W) instead of (A^ X) W (Sec. 3.1 writes
+ * the product A^ H W without fixing the order). The rows that cross the partition boundary are
+ * then rows of T = X W, f_out wide, so this order moves fewer bytes whenever f_out < f_in -
+ * in the messages and in the aggregation alike. fp32 only.
+ *
+ * Forward:
+ *   1. tfull[0:n_loc] = x_local W                                    (dense transform)
+ *   2. cache test of halo_fresh (the owners' current T rows) against cache_sent, message build
+ *      and commit, recovery into tfull[n_loc:]                       (Alg. 2, Sec. 5; f_out wide)
+ *   3. Z = A tfull (optional), H = sigma(Z)                          (aggregation, ReLU fused)
+ */
+typedef struct {
+  const cdf_csr* A;       /* host pointer; n_loc x (n_loc + n_halo) */
+  int32_t n_loc, n_halo, f_in, f_out;
+  int relu;
+  const float* x_local;   /* n_loc x f_in */
+  const float* W;         /* f_in x f_out */
+  float* tfull;           /* (n_loc+n_halo) x f_out: local rows written, halo rows updated in place */
+  const float* halo_fresh; /* n_halo x f_out */
+  float* cache_sent;      /* n_halo x f_out */
+  float eps;
+  cdf_norm norm;
+  int bits;
+  cdf_qscheme qs;
+  cdf_commit commit;
+  int delta;
+  float* Z;               /* out, nullable: n_loc x f_out */
+  float* H;               /* out: n_loc x f_out */
+  uint8_t* mask;          /* out: [n_halo] */
+  int32_t* idx;           /* out: [n_halo] */
+  int32_t* n_sent;        /* out: [1] */
+  uint8_t* codes;         /* out: [n_halo * cdf_code_row_bytes(f_out, bits, qs)] */
+  float* meta;            /* out: [n_halo * 2] */
+} cdf_layer_tf_fwd_args;
+
+int cdf_gcn_layer_tf_fwd(const cdf_layer_tf_fwd_args* args /* host */, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Backward of the transform-first step:
+ *   1. dZ = dH * sigma'(Zs)                                          (kept in the caller's dZ buffer)
+ *   2. dtfull = A^T dZ : rows [0, n_loc) are dT of the local rows, rows [n_loc, ..) the partial
+ *      gradients owed to the halo rows' owners
+ *   3. cache test + message build on those halo gradient rows against gcache_sent
+ *   4. dW = x_local^T dT_local ;  dx_local = dT_local W^T (skipped when dx_local is NULL)
+ */
+typedef struct {
+  const cdf_csr* At;      /* host pointer; (n_loc + n_halo) x n_loc */
+  int32_t n_loc, n_halo, f_in, f_out;
+  int relu;
+  const float* dH;        /* n_loc x f_out */
+  const float* Zs;        /* n_loc x f_out: Z or H of the forward step (unused if !relu) */
+  const float* x_local;   /* n_loc x f_in */
+  const float* W;         /* f_in x f_out */
+  float* dZ;              /* scratch: n_loc x f_out (unused if !relu) */
+  float* dtfull;          /* out: (n_loc+n_halo) x f_out */
+  float* dW;              /* out: f_in x f_out */
+  float* dx_local;        /* out, nullable: n_loc x f_in */
+  float* gcache_sent;     /* n_halo x f_out, updated in place by the commit */
+  float eps;
+  cdf_norm norm;
+  int bits;
+  cdf_qscheme qs;
+  cdf_commit commit;
+  int delta;
+  uint8_t* mask;
+  int32_t* idx;
+  int32_t* n_sent;
+  uint8_t* codes;
+  float* meta;
+} cdf_layer_tf_bwd_args;
+
+int cdf_gcn_layer_tf_bwd(const cdf_layer_tf_bwd_args* args /* host */, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -213,3 +213,38 @@ def layer_bwd(At, n_loc, n_halo, M, Z, dH, W, gcache_sent, eps, norm=NORM_LINF, 
         codes, meta = quantize(dx[n_loc:], gcache_sent, idx, bits, qs, commit, delta)
         out.update(dxfull=dx, mask=mask, idx=idx, codes=codes, meta=meta)
     return out
+
+
+def layer_tf_fwd(A, n_loc, n_halo, x_local, tfull, halo_fresh, cache_sent, W, eps, norm=NORM_LINF, bits=8,
+                 qs=Q_MINMAX, commit=COMMIT_CUR, relu=True, delta=True):
+    """Forward step with the transform applied first: Z = A^ (X W) (Sec. 3.1 leaves the order of
+    the product A^ H W open). The rows exchanged are rows of T = X W.
+    1. tfull[:n_loc] = x_local W
+    2. cache test / message / commit on the owners' fresh T rows, recovery into tfull[n_loc:]
+    3. Z = A^ tfull ; H = sigma(Z)
+    """
+    T, _ = dense_fwd(x_local, W, relu=False)
+    tfull[:n_loc] = T
+    mask, idx = cache_filter(halo_fresh, cache_sent, eps, norm)
+    codes, meta = quantize(halo_fresh, cache_sent, idx, bits, qs, commit, delta)
+    dequantize(codes, meta, idx, tfull[n_loc:], bits, qs, accumulate=delta)
+    Z = spmm(A[0], A[1], A[2], n_loc + n_halo, tfull)
+    H = np.maximum(Z, np.float32(0)) if relu else Z.copy()
+    return dict(mask=mask, idx=idx, codes=codes, meta=meta, Z=Z, H=H)
+
+
+def layer_tf_bwd(At, n_loc, n_halo, x_local, Zs, dH, W, gcache_sent, eps, norm=NORM_LINF, bits=8, qs=Q_MINMAX,
+                 commit=COMMIT_CUR, relu=True, need_dx=True, delta=True):
+    """Backward of the transform-first step.
+    1. dZ = dH * sigma'(Zs)
+    2. dtfull = A^^T dZ : rows [0, n_loc) = dT of local rows, the rest = halo gradient rows
+    3. cache test + message build on the halo gradient rows
+    4. dW = x_local^T dT_local ; dx_local = dT_local W^T
+    """
+    dZ = np.where(Zs > 0, dH, np.float32(0)).astype(np.float32) if relu else np.ascontiguousarray(dH, np.float32)
+    dt = spmm(At[0], At[1], At[2], n_loc, dZ)
+    mask, idx = cache_filter(dt[n_loc:], gcache_sent, eps, norm)
+    codes, meta = quantize(dt[n_loc:], gcache_sent, idx, bits, qs, commit, delta)
+    dW, dX = dense_bwd(x_local, W, np.zeros((n_loc, W.shape[1]), np.float32), dt[:n_loc], relu=False,
+                       need_dm=need_dx)
+    return dict(dZ=dZ, dtfull=dt, mask=mask, idx=idx, codes=codes, meta=meta, dW=dW, dx_local=dX)

@@ -2,4 +2,4 @@
 training: HIP kernels behind a C ABI (libcdf.so) and a thin binding over it."""
 from . import binding  # noqa: F401
 from .binding import *  # noqa: F401,F403
-from .layer import DeviceCsr, LayerBuffers  # noqa: F401
+from .layer import DeviceCsr, LayerBuffers, TfLayerBuffers  # noqa: F401

@@ -22,7 +22,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf_profile_kernel_name", "cdf_profile_read",
            "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_quantize",
            "cdf_dequantize", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
-           "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd"]
+           "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd"]
 
 
 class CdfError(RuntimeError):
@@ -56,6 +56,32 @@ class cdf_layer_bwd_args(ctypes.Structure):
                 ("dW", ctypes.c_void_p), ("dM", ctypes.c_void_p), ("dxfull", ctypes.c_void_p),
                 ("gcache_sent", ctypes.c_void_p), ("eps", ctypes.c_float), ("norm", ctypes.c_int),
                 ("bits", ctypes.c_int), ("qs", ctypes.c_int), ("commit", ctypes.c_int), ("delta", ctypes.c_int),
+                ("mask", ctypes.c_void_p), ("idx", ctypes.c_void_p), ("n_sent", ctypes.c_void_p),
+                ("codes", ctypes.c_void_p), ("meta", ctypes.c_void_p)]
+
+
+class cdf_layer_tf_fwd_args(ctypes.Structure):
+    _fields_ = [("A", ctypes.POINTER(cdf_csr)),
+                ("n_loc", ctypes.c_int32), ("n_halo", ctypes.c_int32), ("f_in", ctypes.c_int32),
+                ("f_out", ctypes.c_int32), ("relu", ctypes.c_int),
+                ("x_local", ctypes.c_void_p), ("W", ctypes.c_void_p), ("tfull", ctypes.c_void_p),
+                ("halo_fresh", ctypes.c_void_p), ("cache_sent", ctypes.c_void_p),
+                ("eps", ctypes.c_float), ("norm", ctypes.c_int), ("bits", ctypes.c_int),
+                ("qs", ctypes.c_int), ("commit", ctypes.c_int), ("delta", ctypes.c_int),
+                ("Z", ctypes.c_void_p), ("H", ctypes.c_void_p),
+                ("mask", ctypes.c_void_p), ("idx", ctypes.c_void_p), ("n_sent", ctypes.c_void_p),
+                ("codes", ctypes.c_void_p), ("meta", ctypes.c_void_p)]
+
+
+class cdf_layer_tf_bwd_args(ctypes.Structure):
+    _fields_ = [("At", ctypes.POINTER(cdf_csr)),
+                ("n_loc", ctypes.c_int32), ("n_halo", ctypes.c_int32), ("f_in", ctypes.c_int32),
+                ("f_out", ctypes.c_int32), ("relu", ctypes.c_int),
+                ("dH", ctypes.c_void_p), ("Zs", ctypes.c_void_p), ("x_local", ctypes.c_void_p), ("W", ctypes.c_void_p),
+                ("dZ", ctypes.c_void_p), ("dtfull", ctypes.c_void_p), ("dW", ctypes.c_void_p),
+                ("dx_local", ctypes.c_void_p), ("gcache_sent", ctypes.c_void_p),
+                ("eps", ctypes.c_float), ("norm", ctypes.c_int), ("bits", ctypes.c_int),
+                ("qs", ctypes.c_int), ("commit", ctypes.c_int), ("delta", ctypes.c_int),
                 ("mask", ctypes.c_void_p), ("idx", ctypes.c_void_p), ("n_sent", ctypes.c_void_p),
                 ("codes", ctypes.c_void_p), ("meta", ctypes.c_void_p)]
 
@@ -217,3 +243,15 @@ def cdf_gcn_layer_bwd(args: cdf_layer_bwd_args, ws):
     rc = load().cdf_gcn_layer_bwd(ctypes.byref(args), _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()),
                                   _stream())
     _check("cdf_gcn_layer_bwd", rc)
+
+
+def cdf_gcn_layer_tf_fwd(args: cdf_layer_tf_fwd_args, ws):
+    rc = load().cdf_gcn_layer_tf_fwd(ctypes.byref(args), _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()),
+                                     _stream())
+    _check("cdf_gcn_layer_tf_fwd", rc)
+
+
+def cdf_gcn_layer_tf_bwd(args: cdf_layer_tf_bwd_args, ws):
+    rc = load().cdf_gcn_layer_tf_bwd(ctypes.byref(args), _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()),
+                                     _stream())
+    _check("cdf_gcn_layer_tf_bwd", rc)

@@ -10,6 +10,23 @@ namespace cdf {
 size_t filter_workspace_bytes(int64_t n_rows);
 size_t spmm_workspace_bytes(int64_t nnz, int32_t dim);
 size_t dense_workspace_bytes(int64_t n, int32_t f, int32_t g);
+int spmm_run(const char* fn, const cdf_csr* A, const void* X, int64_t ldx, void* Y, void* Y2, int64_t ldy,
+             int32_t dim, cdf_dtype dt, void* ws, size_t ws_bytes, hipStream_t st);
+
+// dZ = dH where Zs > 0, else 0 (16 bytes per lane; count is a multiple of 4 or the tail is scalar)
+__global__ __launch_bounds__(256) void relu_mask_kernel(const float* __restrict__ dH, const float* __restrict__ Zs,
+                                                        float* __restrict__ dZ, int64_t count) {
+  const int64_t stride = static_cast<int64_t>(gridDim.x) * blockDim.x;
+  const int64_t quads = count / 4;
+  for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < quads; i += stride) {
+    const float4 g = reinterpret_cast<const float4*>(dH)[i];
+    const float4 z = reinterpret_cast<const float4*>(Zs)[i];
+    reinterpret_cast<float4*>(dZ)[i] =
+        make_float4(z.x > 0.0f ? g.x : 0.0f, z.y > 0.0f ? g.y : 0.0f, z.z > 0.0f ? g.z : 0.0f, z.w > 0.0f ? g.w : 0.0f);
+  }
+  for (int64_t i = quads * 4 + blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < count; i += stride)
+    dZ[i] = Zs[i] > 0.0f ? dH[i] : 0.0f;
+}
 
 static thread_local char g_err[512] = "";
 
@@ -185,4 +202,88 @@ extern "C" int cdf_gcn_layer_bwd(const cdf_layer_bwd_args* p, void* ws, size_t w
                       p->qs, p->commit, p->delta, p->codes, p->meta, stream);
   }
   return rc;
+}
+
+extern "C" int cdf_gcn_layer_tf_fwd(const cdf_layer_tf_fwd_args* p, void* ws, size_t ws_bytes, void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  CDF_REQUIRE(p != nullptr && p->A != nullptr, "cdf_gcn_layer_tf_fwd: null argument block");
+  CDF_REQUIRE(p->n_loc >= 0 && p->n_halo >= 0 && p->f_in > 0 && p->f_out > 0, "cdf_gcn_layer_tf_fwd: bad sizes");
+  CDF_REQUIRE(p->A->n_rows == p->n_loc && p->A->n_cols == p->n_loc + p->n_halo,
+              "cdf_gcn_layer_tf_fwd: adjacency is %d x %d, expected %d x %d", p->A->n_rows, p->A->n_cols, p->n_loc,
+              p->n_loc + p->n_halo);
+  CDF_REQUIRE(p->x_local && p->W && p->tfull && p->H, "cdf_gcn_layer_tf_fwd: null matrix");
+  const size_t fw = filter_workspace_bytes(p->n_halo);
+  const size_t need = fw + spmm_workspace_bytes(p->A->nnz, p->f_out);
+  if (!ws || !aligned(ws, 256) || ws_bytes < need)
+    CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_gcn_layer_tf_fwd: workspace too small or unaligned (%zu < %zu)", ws_bytes, need);
+  char* w = static_cast<char*>(ws);
+  int rc = cdf_dense_fwd(p->x_local, p->f_in, CDF_F32, p->W, p->n_loc, p->f_in, p->f_out, 0, nullptr, p->tfull, stream);
+  if (rc != CDF_OK) return rc;
+  if (p->n_halo > 0) {
+    CDF_REQUIRE(p->halo_fresh && p->cache_sent && p->mask && p->idx && p->n_sent && p->codes && p->meta,
+                "cdf_gcn_layer_tf_fwd: null halo buffer");
+    rc = cdf_cache_filter(p->halo_fresh, p->cache_sent, p->n_halo, p->f_out, p->f_out, CDF_F32, p->eps, p->norm,
+                          p->mask, p->idx, p->n_sent, w, fw, stream);
+    if (rc != CDF_OK) return rc;
+    rc = cdf_quantize(p->halo_fresh, p->cache_sent, p->idx, p->n_sent, p->n_halo, p->f_out, p->f_out, CDF_F32,
+                      p->bits, p->qs, p->commit, p->delta, p->codes, p->meta, stream);
+    if (rc != CDF_OK) return rc;
+    rc = cdf_dequantize(p->codes, p->meta, p->idx, p->n_sent, p->n_halo, p->f_out, p->bits, p->qs,
+                        p->tfull + static_cast<size_t>(p->n_loc) * p->f_out, p->f_out, CDF_F32, p->delta ? 1 : 0, stream);
+    if (rc != CDF_OK) return rc;
+  }
+  // aggregation with the activation fused into the row store
+  if (p->relu)
+    return spmm_run("cdf_gcn_layer_tf_fwd", p->A, p->tfull, p->f_out, p->Z, p->H, p->f_out, p->f_out, CDF_F32, w + fw,
+                    ws_bytes - fw, st);
+  rc = spmm_run("cdf_gcn_layer_tf_fwd", p->A, p->tfull, p->f_out, p->H, nullptr, p->f_out, p->f_out, CDF_F32, w + fw,
+                ws_bytes - fw, st);
+  if (rc == CDF_OK && p->Z && p->n_loc > 0) {
+    if (hipMemcpyAsync(p->Z, p->H, static_cast<size_t>(p->n_loc) * p->f_out * sizeof(float), hipMemcpyDeviceToDevice,
+                       st) != hipSuccess)
+      CDF_FAIL(CDF_ERR_HIP, "cdf_gcn_layer_tf_fwd: copy of Z failed");
+  }
+  return rc;
+}
+
+extern "C" int cdf_gcn_layer_tf_bwd(const cdf_layer_tf_bwd_args* p, void* ws, size_t ws_bytes, void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  CDF_REQUIRE(p != nullptr && p->At != nullptr, "cdf_gcn_layer_tf_bwd: null argument block");
+  CDF_REQUIRE(p->n_loc >= 0 && p->n_halo >= 0 && p->f_in > 0 && p->f_out > 0, "cdf_gcn_layer_tf_bwd: bad sizes");
+  CDF_REQUIRE(p->At->n_rows == p->n_loc + p->n_halo && p->At->n_cols == p->n_loc,
+              "cdf_gcn_layer_tf_bwd: transposed adjacency is %d x %d, expected %d x %d", p->At->n_rows, p->At->n_cols,
+              p->n_loc + p->n_halo, p->n_loc);
+  CDF_REQUIRE(p->dH && p->x_local && p->W && p->dtfull && p->dW && (!p->relu || (p->Zs && p->dZ)),
+              "cdf_gcn_layer_tf_bwd: null matrix");
+  const size_t fw = filter_workspace_bytes(p->n_halo);
+  size_t need = fw + spmm_workspace_bytes(p->At->nnz, p->f_out);
+  need = max_sz(need, fw + dense_workspace_bytes(p->n_loc, p->f_in, p->f_out));
+  if (!ws || !aligned(ws, 256) || ws_bytes < need)
+    CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_gcn_layer_tf_bwd: workspace too small or unaligned (%zu < %zu)", ws_bytes, need);
+  char* w = static_cast<char*>(ws);
+  const float* dz = p->dH;
+  const int64_t count = static_cast<int64_t>(p->n_loc) * p->f_out;
+  if (p->relu && count > 0) {
+    CDF_REQUIRE(aligned(p->dH, 16) && aligned(p->Zs, 16) && aligned(p->dZ, 16), "cdf_gcn_layer_tf_bwd: misaligned matrix");
+    const int64_t blocks = ceil_div(ceil_div(count, 4), 256);
+    relu_mask_kernel<<<static_cast<unsigned>(blocks < 65536 ? (blocks > 0 ? blocks : 1) : 65536), 256, 0, st>>>(
+        p->dH, p->Zs, p->dZ, count);
+    CDF_LAUNCH_CHECK("cdf_gcn_layer_tf_bwd/mask");
+    dz = p->dZ;
+  }
+  int rc = cdf_spmm_bwd(p->At, dz, p->f_out, p->dtfull, p->f_out, p->f_out, CDF_F32, w + fw, ws_bytes - fw, stream);
+  if (rc != CDF_OK) return rc;
+  if (p->n_halo > 0) {
+    CDF_REQUIRE(p->gcache_sent && p->mask && p->idx && p->n_sent && p->codes && p->meta,
+                "cdf_gcn_layer_tf_bwd: null halo buffer");
+    const float* halo_rows = p->dtfull + static_cast<size_t>(p->n_loc) * p->f_out;
+    rc = cdf_cache_filter(halo_rows, p->gcache_sent, p->n_halo, p->f_out, p->f_out, CDF_F32, p->eps, p->norm, p->mask,
+                          p->idx, p->n_sent, w, fw, stream);
+    if (rc != CDF_OK) return rc;
+    rc = cdf_quantize(halo_rows, p->gcache_sent, p->idx, p->n_sent, p->n_halo, p->f_out, p->f_out, CDF_F32, p->bits,
+                      p->qs, p->commit, p->delta, p->codes, p->meta, stream);
+    if (rc != CDF_OK) return rc;
+  }
+  return cdf_dense_bwd(p->x_local, p->f_in, CDF_F32, p->W, nullptr, p->dtfull, p->n_loc, p->f_in, p->f_out, 0, p->dW,
+                       p->dx_local, p->f_in, w + fw, ws_bytes - fw, stream);
 }

@@ -36,8 +36,8 @@ __global__ void chunk_rows_kernel(const int64_t* __restrict__ rowptr, int n_rows
 template <typename T, int EPV, int NP>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
     const int64_t* __restrict__ rowptr, const int* __restrict__ colidx, const float* __restrict__ vals,
-    int n_rows, int64_t nnz, const T* __restrict__ X, int64_t ldx, T* __restrict__ Y, int64_t ldy, int dim,
-    const int* __restrict__ chunk_row, int64_t nchunks, float* __restrict__ phead, float* __restrict__ ptail,
+    int n_rows, int64_t nnz, const T* __restrict__ X, int64_t ldx, T* __restrict__ Y, T* __restrict__ Y2,
+    int64_t ldy, int dim, const int* __restrict__ chunk_row, int64_t nchunks, float* __restrict__ phead, float* __restrict__ ptail,
     int* __restrict__ tail_row, int kChunk) {
   constexpr int U = (8 / NP) > 0 ? (8 / NP) : 1;  // feature rows in flight per wavefront
   const int lane = threadIdx.x & 63;
@@ -85,11 +85,25 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
     }
     cur_end = __builtin_amdgcn_readlane(rel, r - r_base);
   };
+  // a finished row: Y gets the sum (if wanted), Y2 its positive part (if wanted)
   auto store_y = [&](int row) {
-    T* py = Y + static_cast<int64_t>(row) * ldy;
+    if (Y) {
+      T* py = Y + static_cast<int64_t>(row) * ldy;
 #pragma unroll
-    for (int p = 0; p < NP; ++p)
-      if (col_on[p]) VecIO<T, EPV>::store(py + (p * 64 + lane) * EPV, acc[p]);
+      for (int p = 0; p < NP; ++p)
+        if (col_on[p]) VecIO<T, EPV>::store(py + (p * 64 + lane) * EPV, acc[p]);
+    }
+    if (Y2) {
+      T* py = Y2 + static_cast<int64_t>(row) * ldy;
+#pragma unroll
+      for (int p = 0; p < NP; ++p)
+        if (col_on[p]) {
+          float pos[EPV];
+#pragma unroll
+          for (int c = 0; c < EPV; ++c) pos[c] = acc[p][c] > 0.0f ? acc[p][c] : 0.0f;
+          VecIO<T, EPV>::store(py + (p * 64 + lane) * EPV, pos);
+        }
+    }
   };
   auto store_partial = [&](float* buf) {
     float* pp = buf + chunk * static_cast<int64_t>(dim);
@@ -185,8 +199,8 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
 template <typename T, int EPV>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_fixup_kernel(
     const int* __restrict__ chunk_row, const int* __restrict__ tail_row, int64_t nchunks,
-    const float* __restrict__ phead, const float* __restrict__ ptail, T* __restrict__ Y, int64_t ldy, int dim,
-    int n_rows) {
+    const float* __restrict__ phead, const float* __restrict__ ptail, T* __restrict__ Y, T* __restrict__ Y2,
+    int64_t ldy, int dim, int n_rows) {
   const int lane = threadIdx.x & 63;
   const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + (threadIdx.x >> 6);
   if (chunk >= nchunks) return;
@@ -194,7 +208,6 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_fixup_kernel(
   if (r < 0 || r >= n_rows) return;
   int64_t last = chunk;  // last chunk that starts inside row r
   while (last + 1 < nchunks && chunk_row[last + 1] == r) ++last;
-  T* py = Y + static_cast<int64_t>(r) * ldy;
   for (int col = lane * EPV; col < dim; col += 64 * EPV) {
     float acc[EPV];
 #pragma unroll
@@ -214,7 +227,12 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_fixup_kernel(
     for (; c2 <= last; ++c2)
 #pragma unroll
       for (int c = 0; c < EPV; ++c) acc[c] = acc[c] + phead[c2 * static_cast<int64_t>(dim) + col + c];
-    VecIO<T, EPV>::store(py + col, acc);
+    if (Y) VecIO<T, EPV>::store(Y + static_cast<int64_t>(r) * ldy + col, acc);
+    if (Y2) {
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) acc[c] = acc[c] > 0.0f ? acc[c] : 0.0f;
+      VecIO<T, EPV>::store(Y2 + static_cast<int64_t>(r) * ldy + col, acc);
+    }
   }
 }
 
@@ -235,7 +253,7 @@ static int pick_chunk(int64_t nnz) {
 }
 
 template <typename T, int EPV>
-static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, int64_t ldy, int dim, void* ws,
+static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, int64_t ldy, int dim, void* ws,
                        hipStream_t st) {
   const int chunk = pick_chunk(A->nnz);
   const int64_t nc = A->nnz <= 0 ? 1 : ceil_div(A->nnz, chunk);
@@ -257,7 +275,7 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, int64_t 
   const int per_pass = 64 * EPV;
   const int np = static_cast<int>(ceil_div(dim, per_pass));
 #define CDF_SPMM_ARGS                                                                                      \
-  <<<nblocks, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, ldy, dim, \
+  <<<nblocks, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, Y2, ldy, dim, \
                                      chunk_row, nc, phead, ptail, tail_row, chunk)
   prof_begin(K_SPMM, st);
   if (np <= 1) spmm_kernel<T, EPV, 1> CDF_SPMM_ARGS;
@@ -269,25 +287,26 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, int64_t 
   CDF_LAUNCH_CHECK("cdf_spmm/main");
   {
     ProfScope ps(K_SPMM_FIXUP, st);
-    spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, ldy, dim,
+    spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, Y2, ldy, dim,
                                                                  A->n_rows);
   }
   CDF_LAUNCH_CHECK("cdf_spmm/fixup");
   return CDF_OK;
 }
 
-static int spmm_entry(const char* fn, const cdf_csr* A, const void* X, int64_t ldx, void* Y, int64_t ldy,
-                      int32_t dim, cdf_dtype dt, void* ws, size_t ws_bytes, hipStream_t st) {
+// Y = A X and/or Y2 = max(A X, 0); either output may be null, both share ldy.
+int spmm_run(const char* fn, const cdf_csr* A, const void* X, int64_t ldx, void* Y, void* Y2, int64_t ldy,
+             int32_t dim, cdf_dtype dt, void* ws, size_t ws_bytes, hipStream_t st) {
   CDF_REQUIRE(A != nullptr, "%s: matrix is null", fn);
   CDF_REQUIRE(A->n_rows >= 0 && A->n_cols >= 0 && A->nnz >= 0 && dim > 0 && ldx >= dim && ldy >= dim,
               "%s: bad shape rows=%d cols=%d nnz=%lld dim=%d ldx=%lld ldy=%lld", fn, A->n_rows, A->n_cols,
               (long long)A->nnz, dim, (long long)ldx, (long long)ldy);
   if (dt != CDF_F32 && dt != CDF_BF16) CDF_FAIL(CDF_ERR_UNSUPPORTED, "%s: dtype %d", fn, (int)dt);
   if (A->n_rows == 0) return CDF_OK;
-  CDF_REQUIRE(A->rowptr && Y && (A->nnz == 0 || (A->colidx && A->vals && X)), "%s: null pointer", fn);
+  CDF_REQUIRE(A->rowptr && (Y || Y2) && (A->nnz == 0 || (A->colidx && A->vals && X)), "%s: null pointer", fn);
   const size_t esz = elem_bytes(dt);
   CDF_REQUIRE(aligned(A->rowptr, 8) && aligned(A->colidx, 4) && aligned(A->vals, 4) && aligned(X, esz) &&
-                  aligned(Y, esz),
+                  aligned(Y, esz) && aligned(Y2, esz),
               "%s: misaligned pointer", fn);
   if (!ws || !aligned(ws, 256) || ws_bytes < spmm_workspace_bytes(A->nnz, dim))
     CDF_FAIL(CDF_ERR_WORKSPACE, "%s: workspace too small or unaligned (%zu < %zu)", fn, ws_bytes,
@@ -296,7 +315,7 @@ static int spmm_entry(const char* fn, const cdf_csr* A, const void* X, int64_t l
   int epv = dt == CDF_BF16 ? 8 : 4;
   for (; epv > 1; epv >>= 1) {
     const size_t vb = esz * epv;
-    if (dim % epv == 0 && ldx % epv == 0 && ldy % epv == 0 && aligned(X, vb) && aligned(Y, vb)) break;
+    if (dim % epv == 0 && ldx % epv == 0 && ldy % epv == 0 && aligned(X, vb) && aligned(Y, vb) && aligned(Y2, vb)) break;
   }
   const int max_cols = 64 * epv * 8;
   for (int col0 = 0; col0 < dim; col0 += max_cols) {
@@ -304,17 +323,19 @@ static int spmm_entry(const char* fn, const cdf_csr* A, const void* X, int64_t l
     int rc;
     if (dt == CDF_F32) {
       const float* x = static_cast<const float*>(X) + col0;
-      float* y = static_cast<float*>(Y) + col0;
-      rc = epv == 4 ? launch_spmm<float, 4>(A, x, ldx, y, ldy, d, ws, st)
-           : epv == 2 ? launch_spmm<float, 2>(A, x, ldx, y, ldy, d, ws, st)
-                      : launch_spmm<float, 1>(A, x, ldx, y, ldy, d, ws, st);
+      float* y = Y ? static_cast<float*>(Y) + col0 : nullptr;
+      float* y2 = Y2 ? static_cast<float*>(Y2) + col0 : nullptr;
+      rc = epv == 4 ? launch_spmm<float, 4>(A, x, ldx, y, y2, ldy, d, ws, st)
+           : epv == 2 ? launch_spmm<float, 2>(A, x, ldx, y, y2, ldy, d, ws, st)
+                      : launch_spmm<float, 1>(A, x, ldx, y, y2, ldy, d, ws, st);
     } else {
       const bf16_t* x = static_cast<const bf16_t*>(X) + col0;
-      bf16_t* y = static_cast<bf16_t*>(Y) + col0;
-      rc = epv == 8   ? launch_spmm<bf16_t, 8>(A, x, ldx, y, ldy, d, ws, st)
-           : epv == 4 ? launch_spmm<bf16_t, 4>(A, x, ldx, y, ldy, d, ws, st)
-           : epv == 2 ? launch_spmm<bf16_t, 2>(A, x, ldx, y, ldy, d, ws, st)
-                      : launch_spmm<bf16_t, 1>(A, x, ldx, y, ldy, d, ws, st);
+      bf16_t* y = Y ? static_cast<bf16_t*>(Y) + col0 : nullptr;
+      bf16_t* y2 = Y2 ? static_cast<bf16_t*>(Y2) + col0 : nullptr;
+      rc = epv == 8   ? launch_spmm<bf16_t, 8>(A, x, ldx, y, y2, ldy, d, ws, st)
+           : epv == 4 ? launch_spmm<bf16_t, 4>(A, x, ldx, y, y2, ldy, d, ws, st)
+           : epv == 2 ? launch_spmm<bf16_t, 2>(A, x, ldx, y, y2, ldy, d, ws, st)
+                      : launch_spmm<bf16_t, 1>(A, x, ldx, y, y2, ldy, d, ws, st);
     }
     if (rc != CDF_OK) return rc;
   }
@@ -327,10 +348,10 @@ using namespace cdf;
 
 extern "C" int cdf_spmm_fwd(const cdf_csr* A, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t dim,
                             cdf_dtype dt, void* ws, size_t ws_bytes, void* stream) {
-  return spmm_entry("cdf_spmm_fwd", A, X, ldx, Y, ldy, dim, dt, ws, ws_bytes, static_cast<hipStream_t>(stream));
+  return spmm_run("cdf_spmm_fwd", A, X, ldx, Y, nullptr, ldy, dim, dt, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int cdf_spmm_bwd(const cdf_csr* At, const void* dY, int64_t ldy, void* dX, int64_t ldx, int32_t dim,
                             cdf_dtype dt, void* ws, size_t ws_bytes, void* stream) {
-  return spmm_entry("cdf_spmm_bwd", At, dY, ldy, dX, ldx, dim, dt, ws, ws_bytes, static_cast<hipStream_t>(stream));
+  return spmm_run("cdf_spmm_bwd", At, dY, ldy, dX, nullptr, ldx, dim, dt, ws, ws_bytes, static_cast<hipStream_t>(stream));
 }

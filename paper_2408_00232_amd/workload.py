@@ -7,7 +7,7 @@ import torch
 from cdfgen import bench_inputs, configs
 
 from . import binding as B
-from .layer import DeviceCsr, LayerBuffers
+from .layer import DeviceCsr, LayerBuffers, TfLayerBuffers
 
 _TORCH_DT = {"f32": torch.float32, "bf16": torch.bfloat16}
 _QS = {"minmax": B.Q_MINMAX, "symmetric": B.Q_SYMMETRIC, "none": B.Q_NONE}
@@ -15,7 +15,9 @@ _NORM = {"linf": B.NORM_LINF, "l2": B.NORM_L2}
 
 
 class Model:
-    def __init__(self, w: configs.Workload, device="cuda:0", rho=0.37, phi=0.01, partition=None):
+    def __init__(self, w: configs.Workload, device="cuda:0", rho=0.37, phi=0.01, partition=None, order="auto"):
+        """order: "aggregate" = every layer computes (A X) W; "auto" = a layer whose output is
+        narrower than its input computes A (X W) instead (fp32 workloads only)."""
         self.w, self.device = w, device
         P = partition if partition is not None else configs.build_partition(w, device=device)
         self.P = P
@@ -23,9 +25,35 @@ class Model:
         self.A = DeviceCsr(P.n_loc, P.n_loc + P.n_halo, P.rowptr, P.colidx, P.vals, device)
         self.At = DeviceCsr(P.n_loc + P.n_halo, P.n_loc, P.t_rowptr, P.t_colidx, P.t_vals, device)
         dt = _TORCH_DT[w.dtype]
-        self.layers, self.inputs, self.fwd, self.bwd = [], [], [], []
+        self.layers, self.inputs, self.fwd, self.bwd, self.tf = [], [], [], [], []
         dims = w.layers()
         for li, (f_in, f_out) in enumerate(dims):
+            relu = li + 1 < len(dims)
+            tf = order == "auto" and w.dtype == "f32" and f_out < f_in
+            self.tf.append(tf)
+            if tf:
+                L = TfLayerBuffers(self.A, self.At, P.n_loc, P.n_halo, f_in, f_out, bits=w.bits, qs=_QS[w.qscheme],
+                                   device=device, need_dx=True, keep_z=False)
+                I = bench_inputs.make_layer_inputs(w.seed, li, P.n_loc, P.n_halo, f_in, f_out, rho, phi, device, dt,
+                                                   halo_width=f_out)
+                L.x_local.copy_(I.x_local)
+                I.x_local = None
+                L.W.copy_(I.W)
+                L.halo_fresh = None
+                L.dH = None
+                fa, ba = [], []
+                for v in range(2):
+                    a = L.fwd_args(w.eps, _NORM[w.norm], B.COMMIT_CUR, True, relu)
+                    a.halo_fresh = I.fresh[v].data_ptr()
+                    fa.append(a)
+                    b = L.bwd_args(w.eps, _NORM[w.norm], B.COMMIT_CUR, True, relu)
+                    b.dH = I.dH[v].data_ptr()
+                    ba.append(b)
+                self.layers.append(L)
+                self.inputs.append(I)
+                self.fwd.append(fa)
+                self.bwd.append(ba)
+                continue
             L = LayerBuffers(self.A, self.At, P.n_loc, P.n_halo, f_in, f_out, dtype=dt, bits=w.bits,
                              qs=_QS[w.qscheme], device=device, need_dx=True, keep_z=False)
             I = bench_inputs.make_layer_inputs(w.seed, li, P.n_loc, P.n_halo, f_in, f_out, rho, phi, device, dt)
@@ -34,7 +62,6 @@ class Model:
             L.W.copy_(I.W)
             L.halo_fresh = None   # the two versions below replace the single input buffer
             L.dH = None
-            relu = li + 1 < len(dims)
             fa, ba = [], []
             for v in range(2):
                 a = L.fwd_args(w.eps, _NORM[w.norm], B.COMMIT_CUR, True, relu)
@@ -55,9 +82,13 @@ class Model:
         """One pass of the hot path: all layers forward, then all layers backward."""
         v = t & 1
         for li in range(len(self.layers)):
-            B.cdf_gcn_layer_fwd(self.fwd[li][v], self.ws)
+            (B.cdf_gcn_layer_tf_fwd if self.tf[li] else B.cdf_gcn_layer_fwd)(self.fwd[li][v], self.ws)
         for li in reversed(range(len(self.layers))):
-            B.cdf_gcn_layer_bwd(self.bwd[li][v], self.ws)
+            (B.cdf_gcn_layer_tf_bwd if self.tf[li] else B.cdf_gcn_layer_bwd)(self.bwd[li][v], self.ws)
+
+    def spmm_widths(self):
+        """Width of the rows each layer's aggregation gathers (f_out where the layer transforms first)."""
+        return [g if tf else f for (f, g), tf in zip(self.w.layers(), self.tf)]
 
     def edges_per_step(self) -> int:
         return self.nnz * len(self.layers)

@@ -73,7 +73,7 @@ def test_full_size_sampled(oracle, name):
     from paper_2408_00232_amd.workload import Model
     orc = oracle
     w = configs.ALL[name]
-    model = Model(w, DEV)
+    model = Model(w, DEV, order="aggregate")
     P = model.P
     n, h = P.n_loc, P.n_halo
     qs = {"minmax": orc.Q_MINMAX, "symmetric": orc.Q_SYMMETRIC, "none": orc.Q_NONE}[w.qscheme]
@@ -191,3 +191,81 @@ def test_full_size_mid_all_rows(oracle):
     for eps in (0.0, 0.01, 0.1):
         layer_case(cdf, oracle, P, 602, 256, eps, 0, 8, 0, 1, True, True, epochs=2)
     layer_case(cdf, oracle, P, 256, 41, 0.1, 0, 8, 0, 1, True, False, epochs=2)
+
+
+def test_full_size_share_transform_first_layer(oracle):
+    """The benchmark's default launch configuration runs the 256 -> 64 layer of `share` in
+    transform-first order; sampled check of that layer at full size (same scheme as above)."""
+    import paper_2408_00232_amd as cdf
+    from paper_2408_00232_amd.workload import Model
+    orc = oracle
+    w = configs.ALL["share"]
+    model = Model(w, DEV, order="auto")
+    assert model.tf == [False, False, True]
+    P = model.P
+    n, h = P.n_loc, P.n_halo
+    model.step(0)
+    model.step(1)
+    torch.cuda.synchronize()
+    li = 2
+    L, I = model.layers[li], model.inputs[li]
+    ns = int(L.n_sent.item())
+    mask = L.mask[:h]
+    assert ns == int(mask.sum().item())
+    assert torch.equal(L.idx[:ns].long(), torch.nonzero(mask).flatten())
+    assert torch.equal(mask.bool(), I.sent_set)
+    g = torch.Generator(device=DEV).manual_seed(700)
+    S = torch.unique(torch.randint(0, h, (4096,), device=DEV, generator=g))
+    ox, osent, (omask, oidx, ocodes, ometa) = oracle_halo_chain(orc, host(I.fresh[0][S]), host(I.fresh[1][S]), w,
+                                                                orc.Q_MINMAX, orc.NORM_LINF)
+    np.testing.assert_array_equal(host(mask[S]), omask)
+    np.testing.assert_array_equal(host(L.cache_sent[S]), osent)
+    np.testing.assert_array_equal(host(L.tfull[n:][S]), ox)
+    sent_rows = S[torch.from_numpy(oidx).long().to(DEV)]
+    k = torch.searchsorted(L.idx[:ns].long(), sent_rows)
+    np.testing.assert_array_equal(host(L.codes[: ns * L.row_bytes].view(ns, L.row_bytes)[k]), ocodes)
+    # aggregated rows: T of local neighbours from the oracle's own transform, halo T from its chain
+    rows = sample_rows(P.rowptr, n, 192, 8, 701, 3_000_000)
+    ptr, cols, vals = gather_csr_rows(P.rowptr, P.colidx, P.vals, rows)
+    touched, inv = torch.unique(cols, return_inverse=True)
+    is_halo = touched >= n
+    W = host(L.W)
+    tt = np.zeros((touched.numel(), L.f_out), np.float32)
+    t_loc, _ = orc.dense_fwd(host(L.x_local[touched[~is_halo]]), W, relu=False)
+    tt[host(~is_halo)] = t_loc
+    th = touched[is_halo] - n
+    oth, _, _ = oracle_halo_chain(orc, host(I.fresh[0][th]), host(I.fresh[1][th]), w, orc.Q_MINMAX, orc.NORM_LINF)
+    tt[host(is_halo)] = oth
+    oZ = orc.spmm(host(ptr), host(inv.to(torch.int32)), host(vals), touched.numel(), tt)
+    assert_rows_close(host(L.H[rows]), oZ, what="H (last layer: identity)")
+    assert_rows_close(host(L.tfull[touched[~is_halo]]), t_loc, what="T local")
+    # backward on a seeded stand-in for H (relu is off on the last layer, H is unused) from a zero cache
+    L.gcache_sent.zero_()
+    cdf.cdf_gcn_layer_tf_bwd(model.bwd[li][0], model.ws)
+    torch.cuda.synchronize()
+    dH = I.dH[0]
+    trows = sample_rows(P.t_rowptr, n + h, 192, 8, 702, 2_000_000)
+    ptr, cols, vals = gather_csr_rows(P.t_rowptr, P.t_colidx, P.t_vals, trows)
+    touched, inv = torch.unique(cols, return_inverse=True)
+    odt = orc.spmm(host(ptr), host(inv.to(torch.int32)), host(vals), touched.numel(), host(dH[touched]))
+    assert_rows_close(host(L.dtfull[trows]), odt, what="dtfull")
+    # dx_local rows and dW entries from dT rows recomputed by the oracle
+    lrows = trows[trows < n][:128]
+    sel = torch.isin(trows, lrows)
+    _, odx = orc.dense_bwd(host(L.x_local[lrows]), W, np.zeros((lrows.numel(), L.f_out), np.float32),
+                           odt[host(sel)], relu=False)
+    assert_rows_close(host(L.dx_local[lrows]), odx, what="dx_local")
+    gn = int(L.gn_sent.item())
+    nzrow = (L.dtfull[n:] != 0).any(1)
+    assert gn == int(nzrow.sum().item())
+    assert torch.equal(L.gidx[:gn].long(), torch.nonzero(nzrow).flatten())
+    rs = np.random.default_rng(703)
+    gdW = host(L.dW)
+    scale = np.abs(gdW).max()
+    for _ in range(4):
+        i, j = int(rs.integers(L.f_in)), int(rs.integers(L.f_out))
+        want = float(host(L.x_local[:, i].contiguous()).astype(np.float64) @
+                     host(L.dtfull[:n, j].contiguous()).astype(np.float64))
+        assert abs(float(gdW[i, j]) - want) <= 1e-4 * scale
+    del model
+    torch.cuda.empty_cache()

@@ -410,3 +410,88 @@ def test_layer_wide_shrunk_bf16_4bit(cdf, oracle):
     w = configs.shrink(configs.WIDE, 4096)
     P = configs.build_partition(w)
     layer_case(cdf, oracle, P, 1024, 512, 0.05, 0, 4, 0, 1, True, True, epochs=2, dtype=torch.bfloat16)
+
+
+def tf_layer_case(cdf, oracle, P, f_in, f_out, eps, bits, qs, commit, relu, epochs, seed=2):
+    """Transform-first layer against the oracle: forward for several epochs from the same input
+    stream; backward on the oracle's forward results with a gradient cache that keeps every row
+    well away from the threshold."""
+    n, h = P.n_loc, P.n_halo
+    A = cdf.DeviceCsr(n, n + h, P.rowptr, P.colidx, P.vals, DEV)
+    At = cdf.DeviceCsr(n + h, n, P.t_rowptr, P.t_colidx, P.t_vals, DEV)
+    L = cdf.TfLayerBuffers(A, At, n, h, f_in, f_out, bits=bits, qs=qs, device=DEV)
+    ws = torch.zeros(L.workspace_bytes(), dtype=torch.uint8, device=DEV)
+    x_loc = features.normal_matrix(seed, 1, n, f_in)
+    W = features.glorot(seed, 2, f_in, f_out)
+    stream = features.HaloStream(seed, h, f_out)
+    L.x_local.copy_(x_loc)
+    L.W.copy_(W)
+    o_t = np.zeros((n + h, f_out), np.float32)
+    o_sent = np.zeros((h, f_out), np.float32)
+    An, Atn = csr_np(P), csr_np(P, True)
+    for t in range(epochs):
+        fresh = stream.value()
+        dH = features.normal_matrix(seed, 50 + t, n, f_out)
+        L.halo_fresh.copy_(fresh)
+        L.dH.copy_(dH)
+        cdf.cdf_gcn_layer_tf_fwd(L.fwd_args(eps, 0, commit, True, relu), ws)
+        torch.cuda.synchronize()
+        of = oracle.layer_tf_fwd(An, n, h, x_loc.numpy(), o_t, fresh.numpy().copy(), o_sent, W.numpy(), eps, 0, bits,
+                                 qs, commit, relu, True)
+        ns = int(L.n_sent.item())
+        assert ns == of["idx"].size
+        np.testing.assert_array_equal(to_np(L.mask)[:h], of["mask"])
+        np.testing.assert_array_equal(to_np(L.idx)[:ns], of["idx"])
+        np.testing.assert_array_equal(to_np(L.codes)[:ns * L.row_bytes].reshape(ns, -1), of["codes"])
+        np.testing.assert_array_equal(to_np(L.meta)[:ns], of["meta"])
+        np.testing.assert_array_equal(to_np(L.cache_sent), o_sent)
+        np.testing.assert_array_equal(to_np(L.tfull)[n:], o_t[n:])
+        assert_rows_close(to_np(L.tfull)[:n], o_t[:n], what="T local")
+        assert_rows_close(to_np(L.Z), of["Z"], what="Z")
+        assert_rows_close(to_np(L.H), of["H"], what="H")
+        # backward
+        dZ = np.where(of["Z"] > 0, dH.numpy(), np.float32(0)) if relu else dH.numpy()
+        odt = oracle.spmm(*Atn, n, np.ascontiguousarray(dZ, np.float32))
+        gh = odt[n:].astype(np.float64)
+        rs = np.random.default_rng(seed + t)
+        keep = rs.random(h) < (0.5 if eps > 0 else -1.0)
+        factor = np.where(keep, 1.0 + eps * 0.25, 1.0 + eps * 4.0 + 0.5)[:, None]
+        gsent = torch.from_numpy((gh * factor).astype(np.float32))
+        L.Z.copy_(torch.from_numpy(of["Z"]))
+        L.gcache_sent.copy_(gsent)
+        cdf.cdf_gcn_layer_tf_bwd(L.bwd_args(eps, 0, commit, True, relu), ws)
+        torch.cuda.synchronize()
+        o_g = gsent.numpy().copy()
+        ob = oracle.layer_tf_bwd(Atn, n, h, x_loc.numpy(), of["Z"], dH.numpy(), W.numpy(), o_g, eps, 0, bits, qs,
+                                 commit, relu, True, True)
+        assert_rows_close(to_np(L.dtfull), ob["dtfull"], what="dtfull")
+        assert_rows_close(to_np(L.dW), ob["dW"], what="dW")
+        assert_rows_close(to_np(L.dx_local), ob["dx_local"], what="dx_local")
+        gn = int(L.gn_sent.item())
+        np.testing.assert_array_equal(to_np(L.gmask)[:h], ob["mask"])
+        np.testing.assert_array_equal(to_np(L.gidx)[:gn], ob["idx"])
+        if qs != 2 and gn:
+            gc = to_np(L.gcodes)[:gn * L.row_bytes].reshape(gn, -1).astype(np.int32)
+            oc = ob["codes"].astype(np.int32)
+            if bits == 4:
+                gc = np.stack([gc & 15, gc >> 4], -1).reshape(gn, -1)
+                oc = np.stack([oc & 15, oc >> 4], -1).reshape(gn, -1)
+            assert np.abs(gc - oc).max() <= 1 and (gc != oc).mean() < 0.01
+        stream.advance()
+
+
+def test_tf_layer_tiny(cdf, oracle):
+    P = configs.build_partition(configs.TINY)
+    tf_layer_case(cdf, oracle, P, 128, 16, 0.05, 8, 0, 1, True, epochs=3)
+    tf_layer_case(cdf, oracle, P, 16, 8, 0.05, 4, 0, 2, False, epochs=2)
+
+
+def test_tf_layer_mid_shrunk(cdf, oracle):
+    P = configs.build_partition(configs.shrink(configs.MID, 12000))
+    tf_layer_case(cdf, oracle, P, 256, 41, 0.1, 8, 0, 1, False, epochs=2)
+    tf_layer_case(cdf, oracle, P, 602, 256, 0.01, 8, 0, 1, True, epochs=1)
+
+
+def test_tf_layer_large_shrunk(cdf, oracle):
+    P = configs.build_partition(configs.shrink(configs.LARGE, 20000))
+    tf_layer_case(cdf, oracle, P, 256, 64, 0.05, 8, 0, 1, True, epochs=2)

@@ -54,7 +54,8 @@ def test_binding_structs_match_header_layout():
     from paper_2408_00232_amd import binding as B
     text = open(os.path.join(ROOT, "include", "cdf.h")).read()
     for name, cls in (("cdf_layer_fwd_args", B.cdf_layer_fwd_args), ("cdf_layer_bwd_args", B.cdf_layer_bwd_args),
-                      ("cdf_csr", B.cdf_csr)):
+                      ("cdf_layer_tf_fwd_args", B.cdf_layer_tf_fwd_args),
+                      ("cdf_layer_tf_bwd_args", B.cdf_layer_tf_bwd_args), ("cdf_csr", B.cdf_csr)):
         end = re.search(r"\}\s*" + name + ";", text).start()
         body = text[text.rindex("typedef struct {", 0, end) + len("typedef struct {"):end]
         body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)

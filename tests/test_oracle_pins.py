@@ -498,3 +498,92 @@ def test_partitioned_training_step_equals_single_device():
     assert_rows_close(dW1p, dW1, rel=1e-5, frob=2e-6, what="dW1")
     assert_rows_close(dH1p, dH1, rel=2e-5, frob=2e-6, what="dH1")
     assert_rows_close(dW0p, dW0, rel=2e-5, frob=5e-6, what="dW0")
+
+
+# --------------------------------------------------------------------------
+# Transform-first order: Z = A^ (X W)
+# --------------------------------------------------------------------------
+def test_transform_first_matches_dense_and_aggregate_first(oracle):
+    """With exact halo rows both orders give the dense A^ X W, and their parameter gradients obey
+    dW_aggregate_first = X_local^T dT_local + X_halo^T dT_halo (the same sum, regrouped)."""
+    w, g = small_graph(256)
+    Ad = dense_norm_adj(g)
+    rs = np.random.default_rng(31)
+    f, gd = 20, 6
+    X = f32(rs.standard_normal((g.n, f)))
+    W = f32(rs.standard_normal((f, gd)) * 0.3)
+    R = f32(rs.standard_normal((g.n, gd)))
+    Zd = Ad @ X.astype(np.float64) @ W.astype(np.float64)
+    for p in range(4):
+        P = graphs.extract_partition(g, graphs.range_mask(g.n, 4, p))
+        own, halo = P.owned.numpy(), P.halo.numpy()
+        tfull = np.zeros((P.n_loc + P.n_halo, gd), np.float32)
+        T_halo, _ = oracle.dense_fwd(X[halo], W, relu=False)
+        sent = np.zeros((P.n_halo, gd), np.float32)
+        o = oracle.layer_tf_fwd(csr_np(P), P.n_loc, P.n_halo, X[own], tfull, T_halo, sent, W, 0.0,
+                                qs=oracle.Q_NONE, delta=False, relu=True)
+        assert_rows_close(o["Z"], Zd[own], rel=5e-6, frob=2e-6, what="Z transform-first")
+        np.testing.assert_array_equal(o["H"], np.maximum(o["Z"], 0))
+        np.testing.assert_array_equal(tfull[P.n_loc:], T_halo)
+        # aggregate-first on the same partition
+        xfull = np.concatenate([X[own], np.zeros((P.n_halo, f), np.float32)])
+        sent2 = np.zeros((P.n_halo, f), np.float32)
+        a = oracle.layer_fwd(csr_np(P), P.n_loc, P.n_halo, xfull, X[halo].copy(), sent2, W, 0.0,
+                             qs=oracle.Q_NONE, delta=False, relu=True)
+        assert_rows_close(o["Z"], a["Z"], rel=5e-6, frob=2e-6, what="orders agree")
+        # backward: same upstream gradient, mask from the aggregate-first Z for both
+        gs = np.zeros((P.n_halo, gd), np.float32)
+        bt = oracle.layer_tf_bwd(csr_np(P, True), P.n_loc, P.n_halo, X[own], a["Z"], R[own], W, gs, 0.0,
+                                 qs=oracle.Q_NONE, relu=True)
+        gs2 = np.zeros((P.n_halo, f), np.float32)
+        ba = oracle.layer_bwd(csr_np(P, True), P.n_loc, P.n_halo, a["M"], a["Z"], R[own], W, gs2, 0.0,
+                              qs=oracle.Q_NONE, relu=True)
+        dW_regrouped = bt["dW"].astype(np.float64) + X[halo].astype(np.float64).T @ bt["dtfull"][P.n_loc:]
+        assert_rows_close(dW_regrouped, ba["dW"], rel=2e-5, frob=5e-6, what="dW regrouped")
+        # dx_local of the transform-first step equals the local rows of dXfull
+        assert_rows_close(bt["dx_local"], ba["dxfull"][:P.n_loc], rel=2e-5, frob=5e-6, what="dx_local")
+
+
+@pytest.mark.parametrize("relu", [False, True])
+def test_transform_first_backward_matches_finite_differences(oracle, relu):
+    w, g = small_graph(96, seed=7)
+    P = graphs.extract_partition(g, graphs.range_mask(g.n, 3, 2))
+    n, h = P.n_loc, P.n_halo
+    Ad = csr_dense(*csr_np(P), n + h)
+    rs = np.random.default_rng(32)
+    f, gd = 5, 4
+    X = f32(rs.standard_normal((n, f))).astype(np.float64)
+    W = f32(rs.standard_normal((f, gd)) * 0.5).astype(np.float64)
+    Th = f32(rs.standard_normal((h, gd))).astype(np.float64)
+    R = f32(rs.standard_normal((n, gd))).astype(np.float64)
+
+    def loss(Xv, Wv, Tv):
+        Z = Ad @ np.concatenate([Xv @ Wv, Tv])
+        return float(((np.maximum(Z, 0) if relu else Z) * R).sum())
+
+    def fd(arr, which):
+        out = np.zeros_like(arr)
+        for i in range(arr.shape[0]):
+            for j in range(arr.shape[1]):
+                a, b = arr.copy(), arr.copy()
+                a[i, j] += 1e-6
+                b[i, j] -= 1e-6
+                args_a = {"X": X, "W": W, "T": Th}
+                args_b = dict(args_a)
+                args_a[which], args_b[which] = a, b
+                out[i, j] = (loss(args_a["X"], args_a["W"], args_a["T"]) -
+                             loss(args_b["X"], args_b["W"], args_b["T"])) / 2e-6
+        return out
+
+    tfull = np.zeros((n + h, gd), np.float32)
+    sent = np.zeros((h, gd), np.float32)
+    o = oracle.layer_tf_fwd(csr_np(P), n, h, f32(X), tfull, f32(Th), sent, f32(W), 0.0, qs=oracle.Q_NONE,
+                            delta=False, relu=relu)
+    gs = np.zeros((h, gd), np.float32)
+    b = oracle.layer_tf_bwd(csr_np(P, True), n, h, f32(X), o["Z"], f32(R), f32(W), gs, 0.0, qs=oracle.Q_NONE,
+                            relu=relu)
+    tol = lambda ref: 2e-5 * max(1.0, np.abs(ref).max())
+    gW, gX, gT = fd(W, "W"), fd(X, "X"), fd(Th, "T")
+    np.testing.assert_allclose(b["dW"], gW, rtol=0, atol=tol(gW))
+    np.testing.assert_allclose(b["dx_local"], gX, rtol=0, atol=tol(gX))
+    np.testing.assert_allclose(b["dtfull"][n:], gT, rtol=0, atol=tol(gT))
