@@ -195,6 +195,203 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
   if (lane == 0) tail_row[chunk] = tr;
 }
 
+// Column-sliced variant for rows that are several cache lines wide. The feature matrix is
+// processed in vertical slices of SW = LPR * EPV elements (grid.y = slice); within a slice a
+// gather instruction serves 64 / LPR stored entries at once, LPR lanes each. Narrow slices shrink
+// the table the gathers hit by dim / SW, so far more of its rows stay in the 4 MB L2 of an XCD
+// and in the memory-side cache; the CSR arrays are re-read once per slice (8 bytes per entry
+// against SW * 4 of features). Entries of a row are spread round-robin over the lane groups and
+// the groups' partial sums are combined when the row ends - a fixed order, no atomics.
+template <typename T, int EPV, int LPR>
+__global__ __launch_bounds__(kSpmmThreads) void spmm_sliced_kernel(
+    const int64_t* __restrict__ rowptr, const int* __restrict__ colidx, const float* __restrict__ vals,
+    int n_rows, int64_t nnz, const T* __restrict__ X, int64_t ldx, T* __restrict__ Y, T* __restrict__ Y2,
+    int64_t ldy, int dim, const int* __restrict__ chunk_row, int64_t nchunks, float* __restrict__ phead,
+    float* __restrict__ ptail, int* __restrict__ tail_row, int kChunk) {
+  constexpr int EPI = 64 / LPR;  // stored entries per gather instruction
+  constexpr int SW = LPR * EPV;  // slice width in elements
+  constexpr int U = 4;           // gather instructions in flight
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + wave;
+  if (chunk >= nchunks) return;
+  const int g = lane / LPR, lg = lane % LPR;
+  const int col0 = blockIdx.y * SW + lg * EPV;  // this lane's columns: [col0, col0 + EPV)
+  const int64_t s = chunk * kChunk;
+  const int L = static_cast<int>(nnz - s < kChunk ? nnz - s : kChunk);
+  int my_col = 0, krel = 0;
+  float my_val = 0.0f;
+
+  int r = chunk == 0 ? 0 : chunk_row[chunk];
+  bool head = chunk > 0 && rowptr[r] < s;
+  auto load_rel = [&](int rbase) -> int {
+    const int rr = rbase + lane;
+    if (rr < n_rows) {
+      const int64_t d = rowptr[rr + 1] - s;
+      return d > kChunk ? kChunk + 1 : static_cast<int>(d);
+    }
+    return kChunk + 2;
+  };
+  int r_base = r;
+  int rel = load_rel(r_base);
+  int cur_end = __builtin_amdgcn_readlane(rel, 0);
+  auto next_row = [&]() {
+    ++r;
+    if (r - r_base == 64) {
+      r_base = r;
+      rel = load_rel(r_base);
+    }
+    cur_end = __builtin_amdgcn_readlane(rel, r - r_base);
+  };
+
+  float acc[EPV];
+#pragma unroll
+  for (int c = 0; c < EPV; ++c) acc[c] = 0.0f;
+
+  // Combine the lane groups' sums with a halving exchange: at stride 32, 16, ..., LPR each lane
+  // passes one half of its components to its partner and adds the partner's other half, so the
+  // row slice ends up spread over the lanes (FIN components each, starting at component cbase)
+  // with a quarter of the shuffles of a full butterfly. Once a lane is down to one component the
+  // remaining strides are plain sums and only the lanes with the stride bit clear keep the result.
+  constexpr int FIN = EPV / EPI > 0 ? EPV / EPI : 1;
+  int cbase = 0;       // first component (within this lane's EPV) that the lane owns after the exchange
+  bool owner = true;   // false on lanes that hold a duplicate
+  {
+    int cnt = EPV;
+#pragma unroll
+    for (int off = 32; off >= LPR; off >>= 1) {
+      const bool up = (lane & off) != 0;
+      if (cnt > 1) {
+        cnt >>= 1;
+        if (up) cbase += cnt;
+      } else if (up) {
+        owner = false;
+      }
+    }
+  }
+  auto reduce_groups = [&](float (&fin)[FIN]) {
+    float a[EPV];
+#pragma unroll
+    for (int c = 0; c < EPV; ++c) a[c] = acc[c];
+    int cnt = EPV;
+#pragma unroll
+    for (int off = 32; off >= LPR; off >>= 1) {
+      const bool up = (lane & off) != 0;
+      if (cnt > 1) {
+        const int half = cnt >> 1;
+#pragma unroll
+        for (int i = 0; i < EPV / 2; ++i) {
+          if (i < half) {
+            const float send = up ? a[i] : a[half + i];
+            const float keep = up ? a[half + i] : a[i];
+            a[i] = keep + __shfl_xor(send, off, kWave);
+          }
+        }
+        cnt = half;
+      } else {
+        a[0] = a[0] + __shfl_xor(a[0], off, kWave);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < FIN; ++c) fin[c] = a[c];
+  };
+  auto store_y = [&](int row, const float (&fin)[FIN]) {
+    if (!owner) return;
+    const int64_t at = static_cast<int64_t>(row) * ldy + col0 + cbase;
+    if (Y) VecIO<T, FIN>::store(Y + at, fin);
+    if (Y2) {
+      float pos[FIN];
+#pragma unroll
+      for (int c = 0; c < FIN; ++c) pos[c] = fin[c] > 0.0f ? fin[c] : 0.0f;
+      VecIO<T, FIN>::store(Y2 + at, pos);
+    }
+  };
+  auto store_partial = [&](float* buf, const float (&fin)[FIN]) {
+    if (!owner) return;
+    float* pp = buf + chunk * static_cast<int64_t>(dim) + col0 + cbase;
+#pragma unroll
+    for (int c = 0; c < FIN; ++c) pp[c] = fin[c];
+  };
+  auto flush_row = [&]() {
+    float fin[FIN];
+    reduce_groups(fin);
+    if (head) store_partial(phead, fin);
+    else store_y(r, fin);
+    head = false;
+#pragma unroll
+    for (int c = 0; c < EPV; ++c) acc[c] = 0.0f;
+  };
+
+  const T* xs = X + col0;
+  for (int base = 0; base < L; base += 64) {
+    const int cnt = L - base < 64 ? L - base : 64;
+    my_col = 0;
+    my_val = 0.0f;
+    if (lane < cnt) {
+      my_col = colidx[s + base + lane];
+      my_val = vals[s + base + lane];
+    }
+    for (int j = 0; j < cnt; j += EPI * U) {
+      float x[U][EPV];
+      float v[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int e = j + u * EPI + g;  // this group's entry of instruction u
+        const int c = __shfl(my_col, e, kWave);
+        v[u] = __shfl(my_val, e, kWave);
+#pragma unroll
+        for (int q = 0; q < EPV; ++q) x[u][q] = 0.0f;
+        if (e < cnt) VecIO<T, EPV>::load(xs + static_cast<int64_t>(c) * ldx, x[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int first = j + u * EPI;
+        if (first < cnt) {
+          const int avail = cnt - first < EPI ? cnt - first : EPI;
+          int done = 0;
+          while (done < avail) {
+            while (krel == cur_end) {
+              flush_row();
+              next_row();
+            }
+            const int room = cur_end - krel;
+            const int take = avail - done < room ? avail - done : room;
+            if (g >= done && g < done + take) {
+#pragma unroll
+              for (int q = 0; q < EPV; ++q) acc[q] = __fmaf_rn(v[u], x[u][q], acc[q]);
+            }
+            done += take;
+            krel += take;
+          }
+        }
+      }
+    }
+  }
+
+  int tr = -1;
+  if (cur_end > L) {
+    float fin[FIN];
+    reduce_groups(fin);
+    if (head) {
+      store_partial(phead, fin);
+    } else {
+      store_partial(ptail, fin);
+      tr = r;
+    }
+  } else {
+    flush_row();
+    next_row();
+    float zero[FIN];
+#pragma unroll
+    for (int c = 0; c < FIN; ++c) zero[c] = 0.0f;
+    while (r < n_rows && cur_end == L) {
+      store_y(r, zero);
+      next_row();
+    }
+  }
+  if (lane == 0 && blockIdx.y == 0) tail_row[chunk] = tr;
+}
+
 // Adds the pieces of every row that straddles chunk borders, in chunk order.
 template <typename T, int EPV>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_fixup_kernel(
@@ -277,6 +474,28 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, i
 #define CDF_SPMM_ARGS                                                                                      \
   <<<nblocks, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, Y2, ldy, dim, \
                                      chunk_row, nc, phead, ptail, tail_row, chunk)
+  // rows of 64 * EPV elements or more, in whole slices: the column-sliced kernel
+  // (one 128-byte line per row and slice when the element type allows: 8 lanes of 16 bytes)
+  const int lpr = dim % (8 * EPV) == 0 ? 8 : 0;
+  if (lpr > 0 && EPV * static_cast<int>(sizeof(T)) == 16) {
+    const dim3 grid(nblocks, static_cast<unsigned>(dim / (lpr * EPV)));
+    prof_begin(K_SPMM, st);
+#define CDF_SLICED(LPRV)                                                                                        \
+  spmm_sliced_kernel<T, EPV, LPRV><<<grid, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, \
+                                                                  X, ldx, Y, Y2, ldy, dim, chunk_row, nc, phead, \
+                                                                  ptail, tail_row, chunk)
+    CDF_SLICED(8);
+#undef CDF_SLICED
+    prof_end(K_SPMM, st);
+    CDF_LAUNCH_CHECK("cdf_spmm/sliced");
+    {
+      ProfScope ps(K_SPMM_FIXUP, st);
+      spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, Y2, ldy, dim,
+                                                                   A->n_rows);
+    }
+    CDF_LAUNCH_CHECK("cdf_spmm/fixup");
+    return CDF_OK;
+  }
   prof_begin(K_SPMM, st);
   if (np <= 1) spmm_kernel<T, EPV, 1> CDF_SPMM_ARGS;
   else if (np <= 2) spmm_kernel<T, EPV, 2> CDF_SPMM_ARGS;
