@@ -20,7 +20,7 @@
 
 namespace cdf {
 
-constexpr int kRowsPerBlock = 256;  // rows per block in all three kernels
+constexpr int kRowsPerBlock = 64;   // rows per block in all three kernels (16 per wavefront of the test)
 constexpr int kFilterThreads = 256;
 
 template <typename T, int EPV, int NORM>
@@ -35,12 +35,13 @@ __global__ __launch_bounds__(kFilterThreads) void filter_kernel(
   const int sub = lane >> glog;       // which row of the step this lane works on
   const int rows_per_step = 64 >> glog;
   const int nvec = dim / EPV;
-  const int row0 = blockIdx.x * kRowsPerBlock + wave * 64;
+  constexpr int kRowsPerWave = kRowsPerBlock / (kFilterThreads / 64);
+  const int row0 = blockIdx.x * kRowsPerBlock + wave * kRowsPerWave;
   int sent_here = 0;
 
-  for (int s = 0; s < 64; s += rows_per_step) {
+  for (int s = 0; s < kRowsPerWave; s += rows_per_step) {
     const int row = row0 + s + sub;
-    const bool live = row < n_rows;
+    const bool live = row < n_rows && s + sub < kRowsPerWave;  // narrow rows: a step may span more rows than the wave owns
     float accd[NACC][EPV], accc[NACC][EPV];
 #pragma unroll
     for (int a = 0; a < NACC; ++a)

@@ -285,10 +285,14 @@ static void dw_split(int n, int f, int g, int* slab_rows, int* slabs) {
   *slabs = static_cast<int>(ceil_div(n > 0 ? n : 1, rows));
 }
 
+// Upper bound of the slab partials for any n' <= n, f' <= f, g' <= g (so that a workspace sized
+// for the largest layer serves every layer): the split keeps slabs * tiles below about 3072 and
+// a tile's partial is at most 128 x 128 floats; never more than one slab per 2048 rows.
 size_t dense_workspace_bytes(int64_t n, int32_t f, int32_t g) {
-  int sr, sl;
-  dw_split(static_cast<int>(n), f, g, &sr, &sl);
-  return align_up(static_cast<size_t>(sl) * f * g * sizeof(float), 256);
+  const size_t tiles = static_cast<size_t>(ceil_div(f, kBM)) * static_cast<size_t>(ceil_div(g, 64));
+  const size_t by_grid = (3072 + tiles) * static_cast<size_t>(kBM) * 128 * sizeof(float);
+  const size_t by_rows = static_cast<size_t>(ceil_div(n > 0 ? n : 1, 2048)) * f * g * sizeof(float);
+  return align_up(by_grid < by_rows ? by_grid : by_rows, 256);
 }
 
 template <typename T, int MODE>
@@ -351,7 +355,7 @@ extern "C" int cdf_dense_bwd(const void* M, int64_t ldm, cdf_dtype dt, const flo
               "cdf_dense_bwd: misaligned pointer");
   int slab_rows, slabs;
   dw_split(n, f_in, f_out, &slab_rows, &slabs);
-  const size_t need = dense_workspace_bytes(n, f_in, f_out);
+  const size_t need = align_up(static_cast<size_t>(slabs) * f_in * f_out * sizeof(float), 256);
   if (!ws || !aligned(ws, 16) || ws_bytes < need)
     CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_dense_bwd: workspace too small (%zu < %zu)", ws_bytes, need);
   float* part = static_cast<float*>(ws);

@@ -476,7 +476,9 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, i
                                      chunk_row, nc, phead, ptail, tail_row, chunk)
   // rows of 64 * EPV elements or more, in whole slices: the column-sliced kernel
   // (one 128-byte line per row and slice when the element type allows: 8 lanes of 16 bytes)
-  const int lpr = dim % (8 * EPV) == 0 ? 8 : 0;
+  // It pays when rows hold enough entries to amortise the per-row, per-slice reduction and store.
+  constexpr int min_avg = 8;
+  const int lpr = dim % (8 * EPV) == 0 && A->nnz >= static_cast<int64_t>(min_avg) * A->n_rows ? 8 : 0;
   if (lpr > 0 && EPV * static_cast<int>(sizeof(T)) == 16) {
     const dim3 grid(nblocks, static_cast<unsigned>(dim / (lpr * EPV)));
     prof_begin(K_SPMM, st);
