@@ -194,15 +194,12 @@ def main():
 
     # per-kernel durations from the events recorded inside the timed region
     kernels = {}
-    spmm_ms = []
     for k in range(cdf.cdf_profile_kernels()):
         ms = cdf.cdf_profile_read(k)
         if ms:
             name = cdf.cdf_profile_kernel_name(k)
             kernels[name] = {"launches": len(ms), "avg_ms": sum(ms) / len(ms),
-                             "ms_per_step": sum(ms) / args.steps}
-            if name == "spmm_kernel":
-                spmm_ms = ms
+                             "ms_per_step": sum(ms) / args.steps, "_ms": ms}
     # dominant kernel: the aggregation. Launch order within a step: forward layers 0..L-1 on A,
     # then backward layers L-1..0 on A^T; algorithmic bytes differ per launch (feature width).
     esz = 2 if w.dtype == "bf16" else 4
@@ -211,25 +208,46 @@ def main():
     per_step = [spmm_bytes(n, n + h, nnz, f, esz) for f in widths] + \
                [spmm_bytes(n + h, n, nnz, f, esz) for f in reversed(widths)]
     nl = len(per_step)
+    # which launch of a step runs which aggregation kernel (the library slices the columns when the
+    # width is a whole number of 128-byte lines and rows average 8+ entries)
+    line = 64 if w.dtype == "bf16" else 32
+    rows_of = [n] * len(widths) + [n + h] * len(widths)
+    wid_of = list(widths) + list(reversed(widths))
+    kern_of = ["spmm_sliced_kernel" if wd % line == 0 and nnz >= 8 * r else "spmm_kernel"
+               for wd, r in zip(wid_of, rows_of)]
+    times = {k: list(kernels[k]["_ms"]) for k in ("spmm_kernel", "spmm_sliced_kernel") if k in kernels}
+    pos_ms = [[] for _ in range(nl)]
+    ok = all(sum(1 for k in kern_of if k == name) * args.steps == len(ms) for name, ms in times.items())
+    if ok:
+        cursor = {k: 0 for k in times}
+        for _ in range(args.steps):
+            for i, k in enumerate(kern_of):
+                pos_ms[i].append(times[k][cursor[k]])
+                cursor[k] += 1
     roof = None
-    if spmm_ms and len(spmm_ms) == nl * args.steps:
-        bmin = sum(b[0] for b in per_step) / nl
-        bmax = sum(b[1] for b in per_step) / nl
-        avg_s = sum(spmm_ms) / len(spmm_ms) / 1e3
+    if ok and all(pos_ms):
+        spmm_name = max(times, key=lambda k: sum(times[k]))
+        sel = [i for i, k in enumerate(kern_of) if k == spmm_name]
+        bmin = sum(per_step[i][0] for i in sel) / len(sel)
+        bmax = sum(per_step[i][1] for i in sel) / len(sel)
+        avg_s = sum(times[spmm_name]) / len(times[spmm_name]) / 1e3
         # achieved: the aggregation's algorithmic bytes - per stored entry 8 bytes of CSR plus one
         # feature row (dim * element size), plus row pointers and the output rows - over the
         # average launch time. compulsory_*: the same with every input row counted once only.
-        roof = {"kernel": "spmm_kernel", "bound": "hbm", "achieved": bmax / avg_s / 1e9, "peak": HBM_PEAK_GBS,
+        roof = {"kernel": spmm_name, "bound": "hbm", "achieved": bmax / avg_s / 1e9, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": bmax / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
                 "avg_launch_ms": avg_s * 1e3, "algorithmic_bytes_per_launch": bmax,
                 "compulsory_bytes_per_launch": bmin, "compulsory_GBps": bmin / avg_s / 1e9,
-                "launch_ms_by_position": [sum(spmm_ms[i::nl]) / args.steps for i in range(nl)],
-                "algorithmic_GBps_by_position": [per_step[i][1] / (sum(spmm_ms[i::nl]) / args.steps) / 1e6
+                "launches_per_step": len(sel),
+                "aggregation_ms_by_position": [sum(x) / len(x) for x in pos_ms],
+                "aggregation_kernel_by_position": kern_of,
+                "aggregation_width_by_position": wid_of,
+                "algorithmic_GBps_by_position": [per_step[i][1] / (sum(pos_ms[i]) / len(pos_ms[i])) / 1e6
                                                  for i in range(nl)]}
         tfile = os.path.join(ROOT, "profiles", f"traffic_{w.name}.txt")
         if os.path.exists(tfile):
             for line in open(tfile):
-                if line.startswith("spmm_kernel ="):
+                if line.startswith(spmm_name + " ="):
                     f_b, w_b = line.split("=")[1].split()
                     roof["traffic"] = float(f_b) + float(w_b)
 
@@ -275,6 +293,8 @@ def main():
     rho_f = [int(L.n_sent.item()) / max(h, 1) for L in model.layers]
     rho_b = [int(L.gn_sent.item()) / max(h, 1) for L in model.layers]
 
+    for v in kernels.values():
+        v.pop("_ms", None)
     out = {
         "metric": "GCN layer fwd+bwd edges/sec (GE/s) per partition; % of HBM roofline",
         "value": ges, "unit": "GE/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

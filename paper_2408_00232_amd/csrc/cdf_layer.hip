@@ -43,7 +43,7 @@ static size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
 static const char* const kKernelNames[K_COUNT] = {
     "filter_kernel", "scan_kernel", "compact_kernel", "quantize_kernel", "dequantize_kernel",
     "chunk_rows_kernel", "spmm_kernel", "spmm_fixup_kernel", "gemm_kernel<FWD>", "gemm_kernel<DW>",
-    "reduce_slabs_kernel", "gemm_kernel<DM>"};
+    "reduce_slabs_kernel", "gemm_kernel<DM>", "spmm_sliced_kernel", "relu_mask_kernel"};
 constexpr int kProfCap = 8192;
 struct ProfRec {
   int id;
@@ -266,8 +266,11 @@ extern "C" int cdf_gcn_layer_tf_bwd(const cdf_layer_tf_bwd_args* p, void* ws, si
   if (p->relu && count > 0) {
     CDF_REQUIRE(aligned(p->dH, 16) && aligned(p->Zs, 16) && aligned(p->dZ, 16), "cdf_gcn_layer_tf_bwd: misaligned matrix");
     const int64_t blocks = ceil_div(ceil_div(count, 4), 256);
-    relu_mask_kernel<<<static_cast<unsigned>(blocks < 65536 ? (blocks > 0 ? blocks : 1) : 65536), 256, 0, st>>>(
-        p->dH, p->Zs, p->dZ, count);
+    {
+      ProfScope ps(K_RELU_MASK, st);
+      relu_mask_kernel<<<static_cast<unsigned>(blocks < 65536 ? (blocks > 0 ? blocks : 1) : 65536), 256, 0, st>>>(
+          p->dH, p->Zs, p->dZ, count);
+    }
     CDF_LAUNCH_CHECK("cdf_gcn_layer_tf_bwd/mask");
     dz = p->dZ;
   }

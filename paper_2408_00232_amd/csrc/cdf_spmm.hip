@@ -481,14 +481,14 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, i
   const int lpr = dim % (8 * EPV) == 0 && A->nnz >= static_cast<int64_t>(min_avg) * A->n_rows ? 8 : 0;
   if (lpr > 0 && EPV * static_cast<int>(sizeof(T)) == 16) {
     const dim3 grid(nblocks, static_cast<unsigned>(dim / (lpr * EPV)));
-    prof_begin(K_SPMM, st);
+    prof_begin(K_SPMM_SLICED, st);
 #define CDF_SLICED(LPRV)                                                                                        \
   spmm_sliced_kernel<T, EPV, LPRV><<<grid, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, \
                                                                   X, ldx, Y, Y2, ldy, dim, chunk_row, nc, phead, \
                                                                   ptail, tail_row, chunk)
     CDF_SLICED(8);
 #undef CDF_SLICED
-    prof_end(K_SPMM, st);
+    prof_end(K_SPMM_SLICED, st);
     CDF_LAUNCH_CHECK("cdf_spmm/sliced");
     {
       ProfScope ps(K_SPMM_FIXUP, st);
