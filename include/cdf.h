@@ -147,9 +147,10 @@ int cdf_dequantize(const uint8_t* codes, const float* meta, const int32_t* idx, 
 
 /*
  * Aggregation over the normalised adjacency (Sec. 3.1, the product A^_i H of the forward
- * equation): Y[n_rows x dim] = A * X[n_cols x dim], fp32 accumulation in storage order of
- * each row, no atomics, bit-reproducible from run to run. `A` is a HOST pointer to a struct
- * of device arrays. X and Y must not overlap. Empty rows give zero rows.
+ * equation): Y[n_rows x dim] = A * X[n_cols x dim], fp32 accumulation in an order fixed by
+ * the matrix shape alone (no atomics): bit-reproducible from run to run. `A` is a HOST pointer
+ * to a struct of device arrays whose row pointers must be consistent (rowptr[n_rows] == nnz).
+ * X and Y must not overlap. Empty rows give zero rows.
  */
 int cdf_spmm_fwd(const cdf_csr* A, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t dim,
                  cdf_dtype dt, void* ws, size_t ws_bytes, void* stream);

@@ -63,7 +63,7 @@ template <typename T>
 __device__ __forceinline__ void load_quad_fast(const T* p, float (&v)[4]) { VecIO<T, 4>::load(p, v); }
 
 template <typename T, int MODE, int BN, bool FAST>
-__global__ __launch_bounds__(kGemmThreads) void gemm_kernel(GemmArgs a, int a_vec, int b_vec, int m_vec) {
+__global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a_vec, int b_vec, int m_vec) {
   constexpr int SB = BN + 4;
   constexpr int TN = BN / 64;   // 32-wide MFMA tiles per wavefront along n (waves are 2 x 2)
   constexpr int TM = 2;
@@ -287,10 +287,10 @@ static void dw_split(int n, int f, int g, int* slab_rows, int* slabs) {
 
 // Upper bound of the slab partials for any n' <= n, f' <= f, g' <= g (so that a workspace sized
 // for the largest layer serves every layer): the split keeps slabs * tiles below about 3072 and
-// a tile's partial is at most 128 x 128 floats; never more than one slab per 2048 rows.
+// a tile's partial is at most 128 x 256 floats; never more than one slab per 2048 rows.
 size_t dense_workspace_bytes(int64_t n, int32_t f, int32_t g) {
   const size_t tiles = static_cast<size_t>(ceil_div(f, kBM)) * static_cast<size_t>(ceil_div(g, 64));
-  const size_t by_grid = (3072 + tiles) * static_cast<size_t>(kBM) * 128 * sizeof(float);
+  const size_t by_grid = (3072 + tiles) * static_cast<size_t>(kBM) * 256 * sizeof(float);
   const size_t by_rows = static_cast<size_t>(ceil_div(n > 0 ? n : 1, 2048)) * f * g * sizeof(float);
   return align_up(by_grid < by_rows ? by_grid : by_rows, 256);
 }
@@ -299,13 +299,18 @@ template <typename T, int MODE>
 static void launch_gemm(const GemmArgs& a, int Mdim, int Ndim, int slabs, int a_vec, int b_vec, int m_vec,
                         hipStream_t st) {
   ProfScope ps(MODE == GEMM_FWD ? K_GEMM_FWD : MODE == GEMM_DW ? K_GEMM_DW : K_GEMM_DM, st);
-  const int bn = Ndim > 64 ? 128 : 64;
+  // wide outputs: 256 columns per block so that the A operand is read once (the slab-split dW
+  // product has enough blocks already and runs better on 128)
+  const int bn = Ndim > 128 && MODE != GEMM_DW ? 256 : Ndim > 64 ? 128 : 64;
   // reduction length: f_in (FWD), f_out (DM), rows per slab (DW: every slab must be full)
   const int Kdim = MODE == GEMM_FWD ? a.f : MODE == GEMM_DM ? a.g : a.slab_rows;
   const bool k_full = Kdim % kBK == 0 && (MODE != GEMM_DW || a.n % a.slab_rows == 0);
   const bool fast = Mdim % kBM == 0 && Ndim % bn == 0 && k_full && a_vec && b_vec && (!a.relu || MODE == GEMM_FWD || m_vec);
   dim3 grid(static_cast<unsigned>(ceil_div(Mdim, kBM)), static_cast<unsigned>(ceil_div(Ndim, bn)), slabs);
-  if (bn == 128) {
+  if (bn == 256) {
+    if (fast) gemm_kernel<T, MODE, 256, true><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
+    else gemm_kernel<T, MODE, 256, false><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
+  } else if (bn == 128) {
     if (fast) gemm_kernel<T, MODE, 128, true><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
     else gemm_kernel<T, MODE, 128, false><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
   } else {
