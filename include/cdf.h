@@ -330,6 +330,46 @@ typedef struct {
 
 int cdf_gcn_layer_tf_bwd(const cdf_layer_tf_bwd_args* args /* host */, void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * ---- Pieces of the training loop around the layer step ----
+ *
+ * Softmax cross-entropy (the loss of Sec. 7.1) over the rows with 0 <= labels[r] < classes; the
+ * other rows are outside the loss (Sec. 3.1: only owned vertices contribute) and get a zero gradient.
+ *   *loss_sum = sum_r -log softmax(logits[r])[labels[r]]
+ *   dlogits[r] = scale * (softmax(logits[r]) - onehot(labels[r]))
+ *   counts[0] = rows whose largest logit (lowest index on ties) is the label, counts[1] = rows used
+ * logits, dlogits: n x classes fp32 contiguous; labels int32 [n]; loss_sum [1], counts [2] device.
+ * ws: cdf_workspace_bytes(n, classes, 0) is enough. Sums are taken in a fixed order.
+ */
+int cdf_softmax_xent(const float* logits, const int32_t* labels, int32_t n, int32_t classes, float scale,
+                     float* dlogits, float* loss_sum, int32_t* counts, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * One Adam step (the optimiser of Sec. 7.1), t = 1, 2, ...:
+ *   m <- beta1 m + (1-beta1) dW ; v <- beta2 v + (1-beta2) dW^2 ;
+ *   W <- W - lr (m / (1-beta1^t)) / (sqrt(v / (1-beta2^t)) + eps)
+ */
+int cdf_adam_step(float* W, const float* dW, float* m, float* v, int64_t count, float lr, float beta1,
+                  float beta2, float eps, int32_t t, void* stream);
+
+/* dst[i] += src[i] (the owner's "sum with its own value" of Sec. 3.2, and the sum of the
+ * partitions' parameter gradients when several partitions are stepped on one device). */
+int cdf_accumulate(float* dst, const float* src, int64_t count, void* stream);
+
+/*
+ * Threshold controller (Sec. 4.1, the case equation and the moving average). Host function.
+ *   acc < mean - mu1 and eps < nu1 :  eps <- min(lambda1 eps, eps + xi)
+ *   acc > mean + mu2 and eps > nu2 :  eps <- max(lambda2 eps, eps - xi)
+ *   then *mean_acc <- 0.8 *mean_acc + 0.2 acc   (the accuracy is compared with the average of the
+ *   epochs before it). swap_conditions != 0 exchanges the two conditions, which is what the prose
+ *   of Sec. 4.1 describes. p == NULL: the paper's defaults (0.001, 0.02, 0.3, 0.001, 0.01, 1.05, 0.9).
+ */
+typedef struct {
+  float mu1, mu2, nu1, nu2, xi, lambda1, lambda2;
+  int swap_conditions;
+} cdf_eps_params;
+float cdf_eps_update(float eps, float acc, float* mean_acc /* host, in/out */, const cdf_eps_params* p /* host */);
+
 #ifdef __cplusplus
 }
 #endif

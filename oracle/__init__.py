@@ -248,3 +248,42 @@ def layer_tf_bwd(At, n_loc, n_halo, x_local, Zs, dH, W, gcache_sent, eps, norm=N
     dW, dX = dense_bwd(x_local, W, np.zeros((n_loc, W.shape[1]), np.float32), dt[:n_loc], relu=False,
                        need_dm=need_dx)
     return dict(dZ=dZ, dtfull=dt, mask=mask, idx=idx, codes=codes, meta=meta, dW=dW, dx_local=dX)
+
+
+# ----------------------------------------------------------------------------
+# Training-loop pieces (loss, optimiser, threshold controller)
+# ----------------------------------------------------------------------------
+EPS_DEFAULTS = (0.001, 0.02, 0.3, 0.001, 0.01, 1.05, 0.9)   # mu1, mu2, nu1, nu2, xi, lambda1, lambda2 (Sec. 4.1)
+
+
+def softmax_xent(logits, labels, scale: float = 1.0):
+    """-> (loss_sum float, dlogits fp32, n_correct, n_labelled); rows with label < 0 are skipped."""
+    logits = np.ascontiguousarray(logits, np.float32)
+    labels = np.ascontiguousarray(labels, np.int32)
+    n, c = logits.shape
+    d = np.zeros_like(logits)
+    loss = ctypes.c_double(0)
+    nc, nl = ctypes.c_int64(0), ctypes.c_int64(0)
+    rc = lib().orc_softmax_xent(_p(logits), _p(labels), ctypes.c_int32(n), ctypes.c_int32(c), ctypes.c_float(scale),
+                                _p(d), ctypes.byref(loss), ctypes.byref(nc), ctypes.byref(nl))
+    assert rc == 0
+    return loss.value, d, nc.value, nl.value
+
+
+def adam_step(W, dW, m, v, lr, t, beta1=0.9, beta2=0.999, eps=1e-8):
+    """In place on W, m, v (fp32 arrays)."""
+    for a in (W, dW, m, v):
+        assert a.dtype == np.float32 and a.flags.c_contiguous
+    rc = lib().orc_adam_step(_p(W), _p(dW), _p(m), _p(v), ctypes.c_int64(W.size), ctypes.c_float(lr),
+                             ctypes.c_float(beta1), ctypes.c_float(beta2), ctypes.c_float(eps), ctypes.c_int32(t))
+    assert rc == 0
+
+
+def eps_update(eps, acc, mean_acc, params=EPS_DEFAULTS, swap=False):
+    """-> (new eps, new mean_acc)"""
+    fn = lib().orc_eps_update
+    fn.restype = ctypes.c_float
+    arr = (ctypes.c_float * 7)(*params)
+    mean = ctypes.c_float(mean_acc)
+    out = fn(ctypes.c_float(eps), ctypes.c_float(acc), ctypes.byref(mean), arr, ctypes.c_int(1 if swap else 0))
+    return float(out), float(mean.value)

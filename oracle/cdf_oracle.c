@@ -399,3 +399,89 @@ int orc_dense_bwd(const void* M, int64_t ldm, int dt, const float* W, const floa
   }
   return 0;
 }
+
+/* ---------------------------------------------------------------------------
+ * Pieces of the training loop around the layer step (Sec. 7.1: cross-entropy loss, Adam
+ * with learning rate 0.01; Sec. 3.1: the loss is taken on owned (master) vertices only;
+ * Sec. 4.1, last two equations: the threshold controller).
+ * ------------------------------------------------------------------------- */
+
+/* Softmax cross-entropy over the rows with label >= 0 (rows with a negative label are not
+ * in the loss: not owned, or not in the training set).
+ *   loss_sum  = sum_r -log softmax(z_r)[y_r]
+ *   dlogits_r = scale * (softmax(z_r) - onehot(y_r)), zero on skipped rows
+ *   n_correct = rows whose largest logit (lowest index on ties) is the label
+ * All in double, rounded once. */
+int orc_softmax_xent(const float* logits, const int32_t* labels, int32_t n, int32_t classes, float scale,
+                     float* dlogits, double* loss_sum, int64_t* n_correct, int64_t* n_labelled) {
+  double loss = 0.0;
+  int64_t correct = 0, labelled = 0;
+  for (int32_t r = 0; r < n; ++r) {
+    const float* z = logits + (int64_t)r * classes;
+    float* g = dlogits + (int64_t)r * classes;
+    const int y = labels[r];
+    if (y < 0 || y >= classes) {
+      for (int c = 0; c < classes; ++c) g[c] = 0.0f;
+      continue;
+    }
+    int arg = 0;
+    for (int c = 1; c < classes; ++c)
+      if (z[c] > z[arg]) arg = c;
+    double mx = (double)z[arg], s = 0.0;
+    for (int c = 0; c < classes; ++c) s += exp((double)z[c] - mx);
+    loss += log(s) - ((double)z[y] - mx);
+    for (int c = 0; c < classes; ++c) {
+      double p = exp((double)z[c] - mx) / s;
+      g[c] = (float)((double)scale * (p - (c == y ? 1.0 : 0.0)));
+    }
+    correct += arg == y;
+    ++labelled;
+  }
+  *loss_sum = loss;
+  *n_correct = correct;
+  *n_labelled = labelled;
+  return 0;
+}
+
+/* One Adam step (Kingma & Ba): m <- b1 m + (1-b1) g ; v <- b2 v + (1-b2) g^2 ;
+ * W <- W - lr * (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps),  t = 1, 2, ...  */
+int orc_adam_step(float* W, const float* dW, float* m, float* v, int64_t count, float lr, float b1, float b2,
+                  float eps, int32_t t) {
+  const double c1 = 1.0 - pow((double)b1, (double)t), c2 = 1.0 - pow((double)b2, (double)t);
+  for (int64_t i = 0; i < count; ++i) {
+    const double g = (double)dW[i];
+    const double mi = (double)b1 * (double)m[i] + (1.0 - (double)b1) * g;
+    const double vi = (double)b2 * (double)v[i] + (1.0 - (double)b2) * g * g;
+    m[i] = (float)mi;
+    v[i] = (float)vi;
+    W[i] = (float)((double)W[i] - (double)lr * (mi / c1) / (sqrt(vi / c2) + (double)eps));
+  }
+  return 0;
+}
+
+/* Threshold controller (Sec. 4.1, the case equation and the moving average), fp32.
+ * params = { mu1, mu2, nu1, nu2, xi, lambda1, lambda2 }.
+ *   acc < mean - mu1 and eps < nu1 :  eps <- min(lambda1 * eps, eps + xi)
+ *   acc > mean + mu2 and eps > nu2 :  eps <- max(lambda2 * eps, eps - xi)
+ *   otherwise unchanged;  then  mean <- 0.8 * mean + 0.2 * acc.
+ * The accuracy is compared with the average of the epochs before it (the paper does not
+ * say whether the average is updated first). swap != 0 exchanges the two conditions
+ * (the prose of Sec. 4.1 describes relaxing on a large gain and tightening on a small
+ * loss, the opposite of the printed cases). */
+float orc_eps_update(float eps, float acc, float* mean_acc, const float* params, int swap) {
+  const float mu1 = params[0], mu2 = params[1], nu1 = params[2], nu2 = params[3], xi = params[4];
+  const float l1 = params[5], l2 = params[6];
+  const float mean = *mean_acc;
+  const int below = acc < mean - mu1, above = acc > mean + mu2;
+  const int grow = swap ? above : below, shrink = swap ? below : above;
+  float out = eps;
+  if (grow && eps < nu1) {
+    const float a = l1 * eps, b = eps + xi;
+    out = a < b ? a : b;
+  } else if (shrink && eps > nu2) {
+    const float a = l2 * eps, b = eps - xi;
+    out = a > b ? a : b;
+  }
+  *mean_acc = 0.8f * mean + 0.2f * acc;
+  return out;
+}

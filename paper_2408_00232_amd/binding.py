@@ -22,7 +22,8 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf_profile_kernel_name", "cdf_profile_read",
            "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_quantize",
            "cdf_dequantize", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
-           "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd"]
+           "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd",
+           "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_eps_update"]
 
 
 class CdfError(RuntimeError):
@@ -86,6 +87,12 @@ class cdf_layer_tf_bwd_args(ctypes.Structure):
                 ("codes", ctypes.c_void_p), ("meta", ctypes.c_void_p)]
 
 
+class cdf_eps_params(ctypes.Structure):
+    _fields_ = [("mu1", ctypes.c_float), ("mu2", ctypes.c_float), ("nu1", ctypes.c_float), ("nu2", ctypes.c_float),
+                ("xi", ctypes.c_float), ("lambda1", ctypes.c_float), ("lambda2", ctypes.c_float),
+                ("swap_conditions", ctypes.c_int)]
+
+
 _lib = None
 
 
@@ -102,6 +109,7 @@ def load():
         lib.cdf_code_row_bytes.restype = ctypes.c_size_t
         lib.cdf_code_row_bytes.argtypes = [ctypes.c_int32, ctypes.c_int, ctypes.c_int]
         lib.cdf_profile_kernel_name.restype = ctypes.c_char_p
+        lib.cdf_eps_update.restype = ctypes.c_float
         _lib = lib
     return _lib
 
@@ -255,3 +263,30 @@ def cdf_gcn_layer_tf_bwd(args: cdf_layer_tf_bwd_args, ws):
     rc = load().cdf_gcn_layer_tf_bwd(ctypes.byref(args), _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()),
                                      _stream())
     _check("cdf_gcn_layer_tf_bwd", rc)
+
+
+def cdf_softmax_xent(logits, labels, scale, dlogits, loss_sum, counts, ws):
+    rc = load().cdf_softmax_xent(_ptr(logits), _ptr(labels), ctypes.c_int32(logits.shape[0]),
+                                 ctypes.c_int32(logits.shape[1]), ctypes.c_float(scale), _ptr(dlogits), _ptr(loss_sum),
+                                 _ptr(counts), _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()), _stream())
+    _check("cdf_softmax_xent", rc)
+
+
+def cdf_adam_step(W, dW, m, v, lr, t, beta1=0.9, beta2=0.999, eps=1e-8):
+    rc = load().cdf_adam_step(_ptr(W), _ptr(dW), _ptr(m), _ptr(v), ctypes.c_int64(W.numel()), ctypes.c_float(lr),
+                              ctypes.c_float(beta1), ctypes.c_float(beta2), ctypes.c_float(eps), ctypes.c_int32(t),
+                              _stream())
+    _check("cdf_adam_step", rc)
+
+
+def cdf_accumulate(dst, src):
+    assert dst.numel() == src.numel() and dst.is_contiguous() and src.is_contiguous()
+    _check("cdf_accumulate", load().cdf_accumulate(_ptr(dst), _ptr(src), ctypes.c_int64(dst.numel()), _stream()))
+
+
+def cdf_eps_update(eps, acc, mean_acc, params=None):
+    """-> (new eps, new mean_acc); params: cdf_eps_params or None for the paper's defaults."""
+    mean = ctypes.c_float(mean_acc)
+    out = load().cdf_eps_update(ctypes.c_float(eps), ctypes.c_float(acc), ctypes.byref(mean),
+                                ctypes.byref(params) if params is not None else None)
+    return float(out), float(mean.value)

@@ -495,3 +495,46 @@ def test_tf_layer_mid_shrunk(cdf, oracle):
 def test_tf_layer_large_shrunk(cdf, oracle):
     P = configs.build_partition(configs.shrink(configs.LARGE, 20000))
     tf_layer_case(cdf, oracle, P, 256, 64, 0.05, 8, 0, 1, True, epochs=2)
+
+
+@pytest.mark.parametrize("n,classes", [(1000, 8), (777, 41), (300, 64), (130, 47), (64, 1), (500, 200)])
+def test_softmax_xent(cdf, oracle, n, classes):
+    g = torch.Generator().manual_seed(n + classes)
+    logits = torch.randn(n, classes, generator=g) * 3
+    logits[5] = logits[5, 0]                                    # an all-equal row: ties go to class 0
+    labels = torch.randint(-1, classes, (n,), generator=g, dtype=torch.int32)
+    labels[5] = 0
+    d = torch.full((n, classes), 9.0, device=DEV)
+    loss = torch.zeros(1, device=DEV)
+    counts = torch.zeros(2, dtype=torch.int32, device=DEV)
+    ws = ws_for(cdf, n, classes)
+    cdf.cdf_softmax_xent(logits.to(DEV), labels.to(DEV), 0.25, d, loss, counts, ws)
+    torch.cuda.synchronize()
+    ol, od, oc, on = oracle.softmax_xent(logits.numpy(), labels.numpy(), 0.25)
+    assert counts.tolist() == [oc, on]
+    assert abs(float(loss.item()) - ol) <= 1e-5 * max(abs(ol), 1.0)
+    np.testing.assert_allclose(to_np(d), od, rtol=0, atol=2e-6)
+
+
+def test_adam_and_accumulate(cdf, oracle):
+    g = torch.Generator().manual_seed(9)
+    count = 602 * 256 + 3
+    W = torch.randn(count, generator=g)
+    m = torch.zeros(count)
+    v = torch.zeros(count)
+    dW, dm, dv = W.to(DEV), m.to(DEV), v.to(DEV)
+    oW, om, ov = W.numpy().copy(), m.numpy().copy(), v.numpy().copy()
+    for t in range(1, 6):
+        grad = torch.randn(count, generator=g) * (10.0 ** torch.randint(-4, 2, (count,), generator=g).float())
+        cdf.cdf_adam_step(dW, grad.to(DEV), dm, dv, 0.01, t)
+        oracle.adam_step(oW, grad.numpy().copy(), om, ov, 0.01, t)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(to_np(dW), oW, rtol=0, atol=2e-6)
+    np.testing.assert_allclose(to_np(dm), om, rtol=2e-6, atol=1e-6 * np.abs(om).max())   # sums that cancel
+    np.testing.assert_allclose(to_np(dv), ov, rtol=2e-6, atol=1e-6 * np.abs(ov).max())
+    a = torch.randn(count, generator=g)
+    b = torch.randn(count, generator=g)
+    da = a.to(DEV)
+    cdf.cdf_accumulate(da, b.to(DEV))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(da), (a + b).numpy())

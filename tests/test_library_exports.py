@@ -70,3 +70,21 @@ def test_binding_structs_match_header_layout():
             for extra in parts[1:]:
                 fields.append(re.findall(r"[A-Za-z_][A-Za-z0-9_]*", extra)[-1])
         assert fields == [f[0] for f in cls._fields_], name
+
+
+def test_eps_controller_host_function(lib):
+    """The library's controller is host arithmetic: checked here against the hand-worked table."""
+    from paper_2408_00232_amd import binding as B
+    path = os.path.join(ROOT, "tests", "golden", "eps_controller_cases.txt")
+    n = 0
+    for line in open(path):
+        line = line.split("#")[0].strip()
+        if not line:
+            continue
+        eps, acc, mean, want_eps, want_mean = [float(x) for x in line.split("|")]
+        got_eps, got_mean = B.cdf_eps_update(eps, acc, mean)
+        assert abs(got_eps - want_eps) < 2e-7 and abs(got_mean - want_mean) < 2e-7, line
+        n += 1
+    assert n >= 8
+    p = B.cdf_eps_params(0.001, 0.02, 0.3, 0.001, 0.01, 1.05, 0.9, 1)
+    assert abs(B.cdf_eps_update(0.05, 0.60, 0.50, p)[0] - 0.0525) < 2e-7

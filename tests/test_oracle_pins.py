@@ -587,3 +587,69 @@ def test_transform_first_backward_matches_finite_differences(oracle, relu):
     np.testing.assert_allclose(b["dW"], gW, rtol=0, atol=tol(gW))
     np.testing.assert_allclose(b["dx_local"], gX, rtol=0, atol=tol(gX))
     np.testing.assert_allclose(b["dtfull"][n:], gT, rtol=0, atol=tol(gT))
+
+
+# --------------------------------------------------------------------------
+# Training-loop pieces: loss, optimiser, threshold controller
+# --------------------------------------------------------------------------
+def test_softmax_xent_closed_forms_and_gradient(oracle):
+    # uniform logits: loss = ln C per row; gradient = (1/C - onehot)
+    C = 7
+    z = np.zeros((3, C), np.float32)
+    y = np.array([0, 3, -1], np.int32)
+    loss, d, nc, nl = oracle.softmax_xent(z, y)
+    assert abs(loss - 2 * np.log(C)) < 1e-12 and nl == 2
+    assert nc == 1                      # ties: the lowest index wins, so only label 0 counts as correct
+    np.testing.assert_allclose(d[1], np.full(C, 1 / C) - np.eye(C)[3], atol=1e-7)
+    assert not d[2].any()
+    # a dominant logit: loss -> 0, gradient -> 0
+    z = np.full((1, C), -50.0, np.float32)
+    z[0, 2] = 50.0
+    loss, d, nc, nl = oracle.softmax_xent(z, np.array([2], np.int32))
+    assert loss < 1e-30 and np.abs(d).max() < 1e-30 and nc == 1
+    # finite differences of the summed loss
+    rs = np.random.default_rng(41)
+    z = f32(rs.standard_normal((5, C)) * 2)
+    y = np.array([1, 0, 6, -1, 3], np.int32)
+    _, d, _, _ = oracle.softmax_xent(z, y, scale=0.5)
+    for r in range(5):
+        for c in range(C):
+            zp, zm = z.astype(np.float64).copy(), z.astype(np.float64).copy()
+            zp[r, c] += 1e-5
+            zm[r, c] -= 1e-5
+
+            def tot(a):
+                m = a.max(1, keepdims=True)
+                lse = np.log(np.exp(a - m).sum(1)) + m[:, 0]
+                return sum(lse[i] - a[i, y[i]] for i in range(5) if y[i] >= 0)
+            fd = 0.5 * (tot(zp) - tot(zm)) / 2e-5
+            assert abs(d[r, c] - fd) < 2e-6
+
+
+def test_adam_first_steps(oracle):
+    """Step 1 moves every weight by lr * g / (|g| + eps): lr in magnitude when |g| >> eps."""
+    g = f32([0.5, -2.0, 1e-3, 0.0])
+    W = f32([1.0, 1.0, 1.0, 1.0])
+    m = np.zeros(4, np.float32)
+    v = np.zeros(4, np.float32)
+    oracle.adam_step(W, g, m, v, lr=0.01, t=1)
+    np.testing.assert_allclose(W, [0.99, 1.01, 1.0 - 0.01 * 1e-3 / (1e-3 + 1e-8), 1.0], rtol=0, atol=1e-7)
+    np.testing.assert_allclose(m, 0.1 * g, rtol=1e-6)
+    np.testing.assert_allclose(v, 0.001 * g * g, rtol=3e-5)   # beta2 is the fp32 value nearest 0.999
+    # second step with the same gradient: bias-corrected moments still equal g and g^2
+    oracle.adam_step(W, g, m, v, lr=0.01, t=2)
+    np.testing.assert_allclose(W[:2], [0.98, 1.02], rtol=0, atol=2e-7)
+
+
+def test_eps_controller_hand_worked(oracle):
+    rows = read_golden("eps_controller_cases.txt")
+    assert len(rows) >= 8
+    for line in rows:
+        eps, acc, mean, want_eps, want_mean = [float(x) for x in line.split("|")]
+        got_eps, got_mean = oracle.eps_update(eps, acc, mean)
+        assert abs(got_eps - want_eps) < 2e-7 and abs(got_mean - want_mean) < 2e-7, line
+    # the swapped reading exchanges the two actions
+    e, _ = oracle.eps_update(0.05, 0.60, 0.50, swap=True)
+    assert abs(e - 0.0525) < 2e-7
+    e, _ = oracle.eps_update(0.05, 0.40, 0.50, swap=True)
+    assert abs(e - 0.045) < 2e-7
