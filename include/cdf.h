@@ -357,6 +357,19 @@ int cdf_adam_step(float* W, const float* dW, float* m, float* v, int64_t count, 
 int cdf_accumulate(float* dst, const float* src, int64_t count, void* stream);
 
 /*
+ * Row exchange between partitions that are stepped on one device (stands in for the gather /
+ * scatter messages of Sec. 3.2): dst row r = src row idx[r], r < n. idx on the device, every
+ * idx[r] a valid row of src; rows of `dim` elements of type dt; src and dst must not overlap.
+ */
+int cdf_gather_rows(const void* src, int64_t ld_src, const int32_t* idx, int32_t n, int32_t dim,
+                    cdf_dtype dt, void* dst, int64_t ld_dst, void* stream);
+
+/* out[k] = map[idx[k]] for k < min(*n_sent, max_sent): turns the halo-local row list of a
+ * message into the receiver's row numbers before cdf_dequantize applies it there. */
+int cdf_map_index(const int32_t* idx, const int32_t* n_sent, int32_t max_sent, const int32_t* map,
+                  int32_t* out, void* stream);
+
+/*
  * Threshold controller (Sec. 4.1, the case equation and the moving average). Host function.
  *   acc < mean - mu1 and eps < nu1 :  eps <- min(lambda1 eps, eps + xi)
  *   acc > mean + mu2 and eps > nu2 :  eps <- max(lambda2 eps, eps - xi)

@@ -23,7 +23,8 @@ EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf
            "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_quantize",
            "cdf_dequantize", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
            "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd",
-           "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_eps_update"]
+           "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_gather_rows", "cdf_map_index",
+           "cdf_eps_update"]
 
 
 class CdfError(RuntimeError):
@@ -282,6 +283,22 @@ def cdf_adam_step(W, dW, m, v, lr, t, beta1=0.9, beta2=0.999, eps=1e-8):
 def cdf_accumulate(dst, src):
     assert dst.numel() == src.numel() and dst.is_contiguous() and src.is_contiguous()
     _check("cdf_accumulate", load().cdf_accumulate(_ptr(dst), _ptr(src), ctypes.c_int64(dst.numel()), _stream()))
+
+
+def cdf_gather_rows(src, idx, dst):
+    """dst[r] = src[idx[r]] for r < idx.numel(); 2-D row-major tensors of one element type."""
+    assert src.dtype == dst.dtype and src.shape[1] == dst.shape[1] and idx.dtype == torch.int32
+    assert dst.shape[0] >= idx.numel()
+    rc = load().cdf_gather_rows(_ptr(src), ctypes.c_int64(_ld(src)), _ptr(idx), ctypes.c_int32(idx.numel()),
+                                ctypes.c_int32(src.shape[1]), ctypes.c_int(dtype_of(src)), _ptr(dst),
+                                ctypes.c_int64(_ld(dst)), _stream())
+    _check("cdf_gather_rows", rc)
+
+
+def cdf_map_index(idx, n_sent, mapping, out):
+    assert idx.dtype == mapping.dtype == out.dtype == torch.int32 and out.numel() >= idx.numel()
+    rc = load().cdf_map_index(_ptr(idx), _ptr(n_sent), ctypes.c_int32(idx.numel()), _ptr(mapping), _ptr(out), _stream())
+    _check("cdf_map_index", rc)
 
 
 def cdf_eps_update(eps, acc, mean_acc, params=None):

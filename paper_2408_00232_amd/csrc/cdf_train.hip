@@ -135,6 +135,28 @@ __global__ __launch_bounds__(256) void accumulate_kernel(float* __restrict__ dst
     dst[i] = dst[i] + src[i];
 }
 
+// dst row r = src row idx[r], moved in units of U bytes (the widest that divides the row and both
+// leading dimensions). Stands in for the network between partitions stepped on one device.
+template <typename U>
+__global__ __launch_bounds__(256) void gather_rows_kernel(const U* __restrict__ src, int64_t ld_src,
+                                                          const int* __restrict__ idx, int n, int units,
+                                                          U* __restrict__ dst, int64_t ld_dst) {
+  const int64_t total = static_cast<int64_t>(n) * units;
+  for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < total;
+       i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+    const int r = static_cast<int>(i / units), c = static_cast<int>(i - static_cast<int64_t>(r) * units);
+    dst[r * ld_dst + c] = src[idx[r] * ld_src + c];
+  }
+}
+
+__global__ __launch_bounds__(256) void map_index_kernel(const int* __restrict__ idx, const int* __restrict__ n_sent,
+                                                        int max_sent, const int* __restrict__ map,
+                                                        int* __restrict__ out) {
+  int n = *n_sent;
+  n = n < max_sent ? n : max_sent;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) out[i] = map[idx[i]];
+}
+
 static unsigned grid_for(int64_t count) {
   const int64_t b = ceil_div(count, 256);
   return static_cast<unsigned>(b < 1 ? 1 : (b > 65536 ? 65536 : b));
@@ -187,6 +209,40 @@ extern "C" int cdf_accumulate(float* dst, const float* src, int64_t count, void*
   CDF_REQUIRE(dst && src, "cdf_accumulate: null pointer");
   accumulate_kernel<<<grid_for(count), 256, 0, static_cast<hipStream_t>(stream)>>>(dst, src, count);
   CDF_LAUNCH_CHECK("cdf_accumulate");
+  return CDF_OK;
+}
+
+extern "C" int cdf_gather_rows(const void* src, int64_t ld_src, const int32_t* idx, int32_t n, int32_t dim,
+                               cdf_dtype dt, void* dst, int64_t ld_dst, void* stream) {
+  CDF_REQUIRE(n >= 0 && dim > 0, "cdf_gather_rows: bad shape n=%d dim=%d", n, dim);
+  CDF_REQUIRE(dt == CDF_F32 || dt == CDF_BF16, "cdf_gather_rows: unknown element type %d", static_cast<int>(dt));
+  CDF_REQUIRE(ld_src >= dim && ld_dst >= dim, "cdf_gather_rows: leading dimension below the row width");
+  if (n == 0) return CDF_OK;
+  CDF_REQUIRE(src && idx && dst, "cdf_gather_rows: null pointer");
+  const size_t es = dt == CDF_F32 ? 4 : 2;
+  const size_t rb = dim * es, lsb = static_cast<size_t>(ld_src) * es, ldb = static_cast<size_t>(ld_dst) * es;
+  const uintptr_t bits = reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst) | rb | lsb | ldb;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+#define CDF_GATHER(U)                                                                                      \
+  gather_rows_kernel<U><<<grid_for(static_cast<int64_t>(n) * (rb / sizeof(U))), 256, 0, st>>>(             \
+      static_cast<const U*>(src), static_cast<int64_t>(lsb / sizeof(U)), idx, n, static_cast<int>(rb / sizeof(U)), \
+      static_cast<U*>(dst), static_cast<int64_t>(ldb / sizeof(U)))
+  if (bits % 16 == 0) CDF_GATHER(uint4);
+  else if (bits % 8 == 0) CDF_GATHER(uint2);
+  else if (bits % 4 == 0) CDF_GATHER(uint32_t);
+  else CDF_GATHER(uint16_t);
+#undef CDF_GATHER
+  CDF_LAUNCH_CHECK("cdf_gather_rows");
+  return CDF_OK;
+}
+
+extern "C" int cdf_map_index(const int32_t* idx, const int32_t* n_sent, int32_t max_sent, const int32_t* map,
+                             int32_t* out, void* stream) {
+  CDF_REQUIRE(max_sent >= 0, "cdf_map_index: negative capacity");
+  if (max_sent == 0) return CDF_OK;
+  CDF_REQUIRE(idx && n_sent && map && out, "cdf_map_index: null pointer");
+  map_index_kernel<<<grid_for(max_sent), 256, 0, static_cast<hipStream_t>(stream)>>>(idx, n_sent, max_sent, map, out);
+  CDF_LAUNCH_CHECK("cdf_map_index");
   return CDF_OK;
 }
 

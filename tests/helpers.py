@@ -56,3 +56,10 @@ def assert_rows_close(got, want, rel=1e-4, frob=1e-5, what=""):
     assert (err <= rel * ref).all(), f"{what}: row {worst} err {err[worst]:.3e} ref {ref[worst]:.3e}"
     fn = np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30)
     assert fn <= frob, f"{what}: frobenius rel {fn:.3e}"
+
+
+def oracle_parts(parts):
+    """cdfgen partitions -> the oracle training loop's partition records."""
+    from oracle import training
+    return [training.Part(P.n_loc, P.n_halo, P.owned.cpu().numpy(), P.halo.cpu().numpy(), csr_np(P), csr_np(P, True))
+            for P in parts]

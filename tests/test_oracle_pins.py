@@ -653,3 +653,100 @@ def test_eps_controller_hand_worked(oracle):
     assert abs(e - 0.0525) < 2e-7
     e, _ = oracle.eps_update(0.05, 0.40, 0.50, swap=True)
     assert abs(e - 0.045) < 2e-7
+
+
+# --------------------------------------------------------------------------
+# The training loop (Alg. 1) around the layer step
+# --------------------------------------------------------------------------
+def _dense_gcn_training(Ad, X, y, train, Ws, lr, epochs):
+    """Full-graph two-layer GCN, softmax cross-entropy on the train rows, Adam; float64 throughout."""
+    Ws = [w.astype(np.float64) for w in Ws]
+    m = [np.zeros_like(w) for w in Ws]
+    v = [np.zeros_like(w) for w in Ws]
+    rows = np.nonzero(train)[0]
+    out = []
+    for t in range(1, epochs + 1):
+        M1 = Ad @ X
+        Z1 = M1 @ Ws[0]
+        H1 = np.maximum(Z1, 0)
+        M2 = Ad @ H1
+        Z2 = M2 @ Ws[1]
+        zz = Z2[rows] - Z2[rows].max(1, keepdims=True)
+        P = np.exp(zz) / np.exp(zz).sum(1, keepdims=True)
+        loss = -np.log(P[np.arange(rows.size), y[rows]]).mean()
+        acc = (Z2[rows].argmax(1) == y[rows]).mean()
+        dZ2 = np.zeros_like(Z2)
+        P[np.arange(rows.size), y[rows]] -= 1
+        dZ2[rows] = P / rows.size
+        dW1 = M2.T @ dZ2
+        dH1 = Ad.T @ (dZ2 @ Ws[1].T)
+        dW0 = M1.T @ (dH1 * (Z1 > 0))
+        for k, gW in enumerate((dW0, dW1)):
+            m[k] = 0.9 * m[k] + 0.1 * gW
+            v[k] = 0.999 * v[k] + 0.001 * gW * gW
+            Ws[k] = Ws[k] - lr * (m[k] / (1 - 0.9 ** t)) / (np.sqrt(v[k] / (1 - 0.999 ** t)) + 1e-8)
+        out.append(dict(loss=loss, acc=acc, W=[w.copy() for w in Ws], logits=Z2, dW=[dW0, dW1]))
+    return out
+
+
+def test_training_loop_without_cache_equals_full_graph_training(oracle):
+    """Sec. 3.1's equivalence, over whole epochs: with threshold 0 and loss-less difference messages
+    the partitioned loop (forward, loss, backward with gradient messages to the owners, Adam)
+    follows full-graph training on the dense normalised adjacency."""
+    from cdfgen import labels as labelgen
+    from helpers import oracle_parts
+    from oracle import training
+    w, g = small_graph(240, seed=5)
+    n, classes, f0, f1 = g.n, 5, 12, 9
+    Ad = dense_norm_adj(g)
+    y = labelgen.planted_labels(g, classes, 77)
+    X = labelgen.planted_features(y, f0, 77, signal=0.5).numpy()
+    tm = labelgen.train_mask(n, 77).numpy()
+    y = y.numpy()
+    Ws = [features.glorot(77, 70, f0, f1).numpy(), features.glorot(77, 71, f1, classes).numpy()]
+    parts = [graphs.extract_partition(g, graphs.range_mask(n, 3, p)) for p in range(3)]
+    tr = training.Trainer(oracle_parts(parts), [(f0, f1), (f1, classes)], X, y, tm, Ws, eps=0.0, lr=0.01,
+                          adaptive=False, qs=oracle.Q_NONE)
+    ref = _dense_gcn_training(Ad, X.astype(np.float64), y, tm, Ws, 0.01, 4)
+    halo_rows = sum(P.n_halo for P in parts)
+    for t in range(4):
+        st = tr.epoch()
+        assert abs(st["loss"] - ref[t]["loss"]) < 2e-6 * max(1.0, ref[t]["loss"])
+        assert st["train_acc"] == pytest.approx(ref[t]["acc"], abs=1.5 / tm.sum())
+        assert_rows_close(st["logits"], ref[t]["logits"], rel=2e-4, frob=2e-5, what=f"logits {t}")
+        for k in range(2):
+            assert_rows_close(st["dW"][k], ref[t]["dW"][k], rel=5e-4, frob=5e-5, what=f"dW{k} epoch {t}")
+            np.testing.assert_allclose(tr.W[k], ref[t]["W"][k], rtol=0, atol=2e-4)
+        # layer-0 rows never change: after the first epoch only layer 1 sends in the forward pass
+        assert st["sent_fwd"] <= (2 if t == 0 else 1) * halo_rows
+    assert tr.history[1]["sent_fwd"] <= halo_rows
+
+
+def test_training_loop_cache_reduces_messages_and_still_learns(oracle):
+    """Alg. 2 inside the loop: a positive threshold sends fewer rows than threshold 0, the rows
+    each reader aggregates with stay within the threshold of the owners' rows (product form of
+    the test), and the loss still falls."""
+    from cdfgen import labels as labelgen
+    from helpers import oracle_parts
+    from oracle import training
+    w, g = small_graph(240, seed=6)
+    n, classes, f0, f1 = g.n, 4, 10, 8
+    y = labelgen.planted_labels(g, classes, 78)
+    X = labelgen.planted_features(y, f0, 78, signal=0.6).numpy()
+    tm = labelgen.train_mask(n, 78).numpy()
+    Ws = [features.glorot(78, 70, f0, f1).numpy(), features.glorot(78, 71, f1, classes).numpy()]
+    parts = [graphs.extract_partition(g, graphs.range_mask(n, 3, p)) for p in range(3)]
+    runs = {}
+    for eps in (0.0, 0.1):
+        tr = training.Trainer(oracle_parts(parts), [(f0, f1), (f1, classes)], X, y.numpy(), tm, Ws, eps=eps, lr=0.02,
+                              adaptive=False, qs=oracle.Q_NONE)
+        hist = [tr.epoch() for _ in range(12)]
+        runs[eps] = (tr, hist)
+    sent0 = sum(h["sent_fwd"] + h["sent_bwd"] for h in runs[0.0][1])
+    sent1 = sum(h["sent_fwd"] + h["sent_bwd"] for h in runs[0.1][1])
+    assert sent1 < 0.8 * sent0
+    tr, hist = runs[0.1]
+    assert hist[-1]["loss"] < 0.9 * hist[0]["loss"]
+    # staleness of the reader's copy of layer-1 inputs after the last epoch: <= eps * |cached row|
+    for P, xf, c in zip(tr.parts, tr.xfull, tr.cache):
+        np.testing.assert_allclose(xf[1][P.n_loc:], c[1], rtol=0, atol=1e-5)   # reader copy == sender cache
