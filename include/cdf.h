@@ -383,6 +383,44 @@ typedef struct {
 } cdf_eps_params;
 float cdf_eps_update(float eps, float acc, float* mean_acc /* host, in/out */, const cdf_eps_params* p /* host */);
 
+/*
+ * ---- Graph partitioning (host functions, host pointers, no GPU involved) ----
+ *
+ * Hierarchical EBV vertex-cut (Sec. 6): the undirected edges (eu[e], ev[e]), each listed once,
+ * no self pairs, are assigned one after another; edge (u, v) goes to the device i with the
+ * smallest
+ *   (1-gamma) ([i not in d_rep_u] + [i not in d_rep_v]) + gamma ([host_i not in h_rep_u] + [host_i not in h_rep_v])
+ *   + alpha e_count[i] / (|E|/p) + beta v_count[i] / (|V|/p)                       (double arithmetic,
+ * terms added left to right; the lowest i wins ties), host_i = i / devices_per_host. d_rep / h_rep are
+ * the devices / hosts a vertex already has a replica on, e_count / v_count the edges / vertex replicas
+ * assigned to a device so far. sort_edges != 0 processes the edges by ascending sum of their end
+ * vertices' degrees (stable; the order of the EBV algorithm the section builds on), otherwise as given.
+ * gamma = 0 is plain EBV. part [n_edges] receives the device of every edge. p <= 64.
+ */
+typedef struct {
+  int32_t p, devices_per_host;
+  double alpha, beta, gamma;
+  int sort_edges;
+} cdf_ebv_params;
+int cdf_ebv_partition(int64_t n_vertices, int64_t n_edges, const int64_t* eu, const int64_t* ev,
+                      const cdf_ebv_params* prm, int32_t* part);
+
+/*
+ * Statistics of a vertex-cut (Sec. 6: replication factor sum|V_i| / |V|, edge imbalance
+ * max|E_i| / (|E|/p), vertex imbalance max|V_i| / (sum|V_i|/p); Sec. 7 ablation: the largest number of
+ * messages one device sends inside its host / across hosts per exchange, counting one gather message per
+ * mirror and one scatter message per mirror of each of its masters). The master of a vertex is the replica
+ * holding most of its edges (lowest device on ties; a vertex without edges lives on device v mod p);
+ * master [n_vertices] is written when not NULL.
+ */
+typedef struct {
+  double replication_factor, edge_imbalance, vertex_imbalance;
+  int64_t max_inner, max_outer, replicas_total;
+} cdf_cut_stats;
+int cdf_cut_statistics(int64_t n_vertices, int64_t n_edges, const int64_t* eu, const int64_t* ev,
+                       const int32_t* part, int32_t p, int32_t devices_per_host, int32_t* master,
+                       cdf_cut_stats* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf
            "cdf_dequantize", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
            "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd",
            "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_gather_rows", "cdf_map_index",
-           "cdf_eps_update"]
+           "cdf_eps_update", "cdf_ebv_partition", "cdf_cut_statistics"]
 
 
 class CdfError(RuntimeError):
@@ -307,3 +307,41 @@ def cdf_eps_update(eps, acc, mean_acc, params=None):
     out = load().cdf_eps_update(ctypes.c_float(eps), ctypes.c_float(acc), ctypes.byref(mean),
                                 ctypes.byref(params) if params is not None else None)
     return float(out), float(mean.value)
+
+
+class cdf_ebv_params(ctypes.Structure):
+    _fields_ = [("p", ctypes.c_int32), ("devices_per_host", ctypes.c_int32), ("alpha", ctypes.c_double),
+                ("beta", ctypes.c_double), ("gamma", ctypes.c_double), ("sort_edges", ctypes.c_int)]
+
+
+class cdf_cut_stats(ctypes.Structure):
+    _fields_ = [("replication_factor", ctypes.c_double), ("edge_imbalance", ctypes.c_double),
+                ("vertex_imbalance", ctypes.c_double), ("max_inner", ctypes.c_int64), ("max_outer", ctypes.c_int64),
+                ("replicas_total", ctypes.c_int64)]
+
+
+def _host_i64(t):
+    assert not t.is_cuda and t.dtype == torch.int64 and t.is_contiguous()
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def cdf_ebv_partition(n_vertices, eu, ev, p, devices_per_host=1, alpha=1.0, beta=1.0, gamma=0.1, sort_edges=True):
+    """Host tensors eu, ev (int64, one entry per undirected edge) -> int32 [n_edges] device of every edge."""
+    part = torch.zeros(eu.numel(), dtype=torch.int32)
+    prm = cdf_ebv_params(p, devices_per_host, alpha, beta, gamma, 1 if sort_edges else 0)
+    rc = load().cdf_ebv_partition(ctypes.c_int64(n_vertices), ctypes.c_int64(eu.numel()), _host_i64(eu), _host_i64(ev),
+                                  ctypes.byref(prm), ctypes.c_void_p(part.data_ptr()))
+    _check("cdf_ebv_partition", rc)
+    return part
+
+
+def cdf_cut_statistics(n_vertices, eu, ev, part, p, devices_per_host=1):
+    """-> (cdf_cut_stats, master int32 [n_vertices]) for host tensors."""
+    assert part.dtype == torch.int32 and not part.is_cuda and part.is_contiguous()
+    master = torch.zeros(n_vertices, dtype=torch.int32)
+    st = cdf_cut_stats()
+    rc = load().cdf_cut_statistics(ctypes.c_int64(n_vertices), ctypes.c_int64(eu.numel()), _host_i64(eu), _host_i64(ev),
+                                   ctypes.c_void_p(part.data_ptr()), ctypes.c_int32(p), ctypes.c_int32(devices_per_host),
+                                   ctypes.c_void_p(master.data_ptr()), ctypes.byref(st))
+    _check("cdf_cut_statistics", rc)
+    return st, master

@@ -1,0 +1,133 @@
+"""Hierarchical EBV partitioner (Sec. 6): pins of the oracle, then the library's host function against
+the oracle, edge by edge. No GPU is involved anywhere in this file."""
+import numpy as np
+import pytest
+import torch
+
+from cdfgen import configs
+from oracle import partition as op
+
+
+def _edges(g):
+    return list(zip(g.lo.tolist(), g.hi.tolist()))
+
+
+# ---------------------------------------------------------------- pins of the oracle
+def test_first_edges_by_hand():
+    """Path 0-1-2-3 plus edge 0-2, p = 2, one host, alpha = beta = 1, gamma = 0, listed order.
+    e0 (0,1): both devices empty, all terms tie -> device 0.          e_count=[1,0] v_count=[2,0]
+    e1 (1,2): dev0: 1 miss + 1/2.5 + 2/2 = 2.4 ; dev1: 2 misses = 2.0 -> device 1.   [1,1] [2,2]
+    e2 (2,3): dev0: 2 + .4 + 1 = 3.4 ; dev1: 1 + .4 + 1 = 2.4 -> device 1.          [1,2] [2,3]
+    e3 (0,2): dev0: 1 + .4 + 1 = 2.4 ; dev1: 1 + .8 + 1.5 = 3.3 -> device 0.
+    e4 (0,3): dev0: 1 + .8 + 1.5 (v_count 3) = 3.3 ; dev1: 1 + .8 + 1.5 = 3.3 -> tie -> device 0."""
+    edges = [(0, 1), (1, 2), (2, 3), (0, 2), (0, 3)]
+    assert op.ebv_partition(4, edges, 2, 1, 1.0, 1.0, 0.0, sort_edges=False) == [0, 1, 1, 0, 0]
+
+
+def test_without_balance_terms_everything_follows_the_first_edge():
+    """alpha = beta = 0 on a connected graph listed in BFS order: once device 0 holds one end of an
+    edge, it has the fewest misses or ties, and ties go to the lowest device."""
+    edges = [(0, 1), (0, 2), (1, 3), (2, 4), (3, 4), (4, 5)]
+    assert op.ebv_partition(6, edges, 4, 1, 0.0, 0.0, 0.0, sort_edges=False) == [0] * 6
+
+
+def test_balance_term_alone_deals_round_robin():
+    """Only the edge-count term (replica terms switched off by gamma = 1 on one host, where every
+    host term is equal across devices): edges are dealt to the least loaded device, lowest first."""
+    edges = [(i, i + 1) for i in range(12)]
+    part = op.ebv_partition(13, edges, 4, 4, 1.0, 0.0, 1.0, sort_edges=False)
+    assert part == [0, 1, 2, 3] * 3
+
+
+def test_sorted_order_is_by_degree_sum_and_stable():
+    """Star with centre 0 plus a far edge (5,6): the far edge has the smallest degree sum and is
+    assigned first although it is listed last; with alpha = beta = 0 it takes device 0, and the star
+    edges (all tied at 2 misses, nothing shared with it) follow the first of them."""
+    edges = [(0, 1), (0, 2), (0, 3), (0, 4), (5, 6)]
+    a = op.ebv_partition(7, edges, 3, 1, 1.0, 0.0, 0.0, sort_edges=True)
+    # (5,6) first -> dev 0 (e_count [1,0,0]); (0,1): misses tie, edge term favours dev 1; then the star
+    # stays where vertex 0 is until the edge term (1/(5/3) = .6 per edge) outweighs one miss (1.0):
+    # (0,2): dev1 1 miss + .6 = 1.6 vs dev0 2 + .6 = 2.6 vs dev2 2.0 -> dev1; (0,3): dev1 1 + 1.2 = 2.2 vs dev2 2.0 -> dev2
+    # (0,4): dev0 2.6 ; dev1 1 + 1.2 = 2.2 ; dev2 1 + .6 = 1.6 -> dev2
+    assert a == [1, 1, 2, 2, 0]
+
+
+def test_hierarchy_term_prefers_the_host_that_already_has_the_vertex():
+    """p = 4 on 2 hosts (devices 0,1 | 2,3), alpha = 3, beta = 0, listed order, |E|/p = 1.5 so one edge
+    of load costs 2. Three disjoint edges go to devices 0, 1, 2 - the third is (0,1), which puts vertex 0
+    on device 2 - and (7,8) to device 3. (0,9): device 2 has one miss, 1 + 2 = 3, the others 4 or more
+    -> device 2, now loaded twice. (0,10): device 2 costs 1 + 4 = 5; devices 0 and 1 cost 2 + 2 = 4;
+    device 3 costs (1-g)*2 + g*1 + 2 = 4 - g, because its host already has vertex 0.
+    g = 0: tie at 4 -> lowest device 0.   g = 0.1: device 3."""
+    edges = [(3, 4), (5, 6), (0, 1), (7, 8), (0, 9), (0, 10)]
+    assert op.ebv_partition(11, edges, 4, 2, 3.0, 0.0, 0.0, sort_edges=False) == [0, 1, 2, 3, 2, 0]
+    assert op.ebv_partition(11, edges, 4, 2, 3.0, 0.0, 0.1, sort_edges=False) == [0, 1, 2, 3, 2, 3]
+
+
+def test_statistics_on_a_hand_graph():
+    """Triangle 0-1-2 and pendant 2-3, p = 2 (one host each): edges (0,1),(1,2) on device 0, (0,2),(2,3) on 1.
+    V_0 = {0,1,2}, V_1 = {0,2,3}; vertex 4 has no edge and lives on device 0 (4 mod 2).
+    replicas = 3 + 3 + 1 = 7, RF = 7/5; |E_i| = 2, 2 -> edge IF 1; |V_i| = 4, 3 -> vertex IF 4/3.5.
+    masters: 0 -> tie (1,1) -> device 0; 1 -> 0; 2 -> 1 (two edges there); 3 -> 1; 4 -> 0.
+    cut vertices 0 and 2: each gives one gather and one scatter message; device 0 sends gather for 2 and
+    scatter for 0 = 2 messages, device 1 likewise; hosts differ -> outer = 2, inner = 0."""
+    edges = [(0, 1), (1, 2), (0, 2), (2, 3)]
+    st = op.cut_statistics(5, edges, [0, 0, 1, 1], 2, 1)
+    assert st["master"] == [0, 0, 1, 1, 0]
+    assert st["replicas_total"] == 7 and st["replication_factor"] == pytest.approx(1.4)
+    assert st["edge_imbalance"] == pytest.approx(1.0) and st["vertex_imbalance"] == pytest.approx(4 / 3.5)
+    assert (st["max_inner"], st["max_outer"]) == (0, 2)
+    st = op.cut_statistics(5, edges, [0, 0, 1, 1], 2, 2)       # both devices on one host
+    assert (st["max_inner"], st["max_outer"]) == (2, 0)
+
+
+def test_invariants_on_a_power_law_graph():
+    """Every edge gets exactly one device in range; 1 <= RF <= p; edge imbalance close to 1 with the
+    default weights (the paper's tables report 1.00-1.01); gamma > 0 does not raise outer connections."""
+    w = configs.shrink(configs.MID, 600)
+    g = configs.build_graph(w)
+    edges = _edges(g)
+    out = {}
+    for gamma in (0.0, 0.1):
+        part = op.ebv_partition(g.n, edges, 8, 4, 1.0, 1.0, gamma)
+        assert len(part) == len(edges) and all(0 <= i < 8 for i in part)
+        st = op.cut_statistics(g.n, edges, part, 8, 4)
+        assert 1.0 <= st["replication_factor"] <= 8.0
+        assert st["edge_imbalance"] < 1.05
+        out[gamma] = st
+    assert out[0.1]["max_outer"] <= out[0.0]["max_outer"]
+
+
+# ---------------------------------------------------------------- library host function vs oracle
+@pytest.mark.parametrize("p,dph,gamma,sort_edges", [(4, 1, 0.0, True), (8, 4, 0.1, True), (8, 2, 0.3, False),
+                                                     (3, 1, 0.0, False), (64, 8, 0.1, True)])
+def test_library_partitioner_equals_oracle(p, dph, gamma, sort_edges):
+    from paper_2408_00232_amd import binding as B
+    w = configs.shrink(configs.MID, 500)
+    g = configs.build_graph(w)
+    edges = _edges(g)
+    want = op.ebv_partition(g.n, edges, p, dph, 1.0, 1.0, gamma, sort_edges)
+    got = B.cdf_ebv_partition(g.n, g.lo.contiguous(), g.hi.contiguous(), p, dph, 1.0, 1.0, gamma, sort_edges)
+    assert got.tolist() == want
+    st, master = B.cdf_cut_statistics(g.n, g.lo.contiguous(), g.hi.contiguous(), got, p, dph)
+    ref = op.cut_statistics(g.n, edges, want, p, dph)
+    assert master.tolist() == ref["master"]
+    assert st.replicas_total == ref["replicas_total"]
+    assert (st.max_inner, st.max_outer) == (ref["max_inner"], ref["max_outer"])
+    assert st.replication_factor == pytest.approx(ref["replication_factor"], rel=1e-12)
+    assert st.edge_imbalance == pytest.approx(ref["edge_imbalance"], rel=1e-12)
+    assert st.vertex_imbalance == pytest.approx(ref["vertex_imbalance"], rel=1e-12)
+
+
+def test_library_partitioner_rejects_bad_input():
+    from paper_2408_00232_amd import binding as B
+    eu, ev = torch.tensor([0, 1]), torch.tensor([1, 1])
+    with pytest.raises(B.CdfError):
+        B.cdf_ebv_partition(3, eu, ev, 2)                       # self pair
+    with pytest.raises(B.CdfError):
+        B.cdf_ebv_partition(3, torch.tensor([0]), torch.tensor([5]), 2)   # endpoint out of range
+    with pytest.raises(B.CdfError):
+        B.cdf_ebv_partition(3, torch.tensor([0]), torch.tensor([1]), 65)  # more than 64 devices
+    with pytest.raises(B.CdfError):
+        B.cdf_ebv_partition(3, torch.tensor([0]), torch.tensor([1]), 6, 4)  # hosts do not divide
+    assert B.cdf_ebv_partition(3, torch.zeros(0, dtype=torch.int64), torch.zeros(0, dtype=torch.int64), 2).numel() == 0
