@@ -370,6 +370,28 @@ int cdf_map_index(const int32_t* idx, const int32_t* n_sent, int32_t max_sent, c
                   int32_t* out, void* stream);
 
 /*
+ * ---- Pieces of the master / mirror exchange of the vertex-cut framing (Sec. 3.2, Alg. 2 in full) ----
+ *
+ * "active vertex u" (Alg. 2): flags[(map ? map[idx[k]] : idx[k]) + offset] = 1 for k < min(*n_sent, max_sent).
+ * flags is a byte array the caller cleared; map may be NULL.
+ */
+int cdf_mark_rows(const int32_t* idx, const int32_t* n_sent, int32_t max_sent, const int32_t* map,
+                  int32_t offset, uint8_t* flags, void* stream);
+
+/*
+ * The mirrors of active vertices (Alg. 2, last loop: the cached total of every active vertex goes to
+ * its mirrors): mask[r] = flags[map[r]] != 0 for r < n_rows, idx = the ascending list of such r,
+ * *n_sent their number. map[r] is the flag position of the master of mirror row r.
+ * ws as for cdf_cache_filter.
+ */
+int cdf_active_rows(const uint8_t* flags, const int32_t* map, int32_t n_rows, uint8_t* mask, int32_t* idx,
+                    int32_t* n_sent, void* ws, size_t ws_bytes, void* stream);
+
+/* h[i] = max(z[i], 0): the activation applied after the exchange has combined the partial sums
+ * (Sec. 3.1, H = sigma(Z), with Z only complete once Alg. 2 has run). */
+int cdf_relu_fwd(const float* z, float* h, int64_t count, void* stream);
+
+/*
  * Threshold controller (Sec. 4.1, the case equation and the moving average). Host function.
  *   acc < mean - mu1 and eps < nu1 :  eps <- min(lambda1 eps, eps + xi)
  *   acc > mean + mu2 and eps > nu2 :  eps <- max(lambda2 eps, eps - xi)

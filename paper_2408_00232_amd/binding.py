@@ -24,6 +24,7 @@ EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf
            "cdf_dequantize", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
            "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd",
            "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_gather_rows", "cdf_map_index",
+           "cdf_mark_rows", "cdf_active_rows", "cdf_relu_fwd",
            "cdf_eps_update", "cdf_ebv_partition", "cdf_cut_statistics"]
 
 
@@ -299,6 +300,25 @@ def cdf_map_index(idx, n_sent, mapping, out):
     assert idx.dtype == mapping.dtype == out.dtype == torch.int32 and out.numel() >= idx.numel()
     rc = load().cdf_map_index(_ptr(idx), _ptr(n_sent), ctypes.c_int32(idx.numel()), _ptr(mapping), _ptr(out), _stream())
     _check("cdf_map_index", rc)
+
+
+def cdf_mark_rows(idx, n_sent, mapping, offset, flags):
+    assert idx.dtype == torch.int32 and flags.dtype == torch.uint8
+    rc = load().cdf_mark_rows(_ptr(idx), _ptr(n_sent), ctypes.c_int32(idx.numel()), _ptr(mapping), ctypes.c_int32(offset),
+                              _ptr(flags), _stream())
+    _check("cdf_mark_rows", rc)
+
+
+def cdf_active_rows(flags, mapping, mask, idx, n_sent, ws):
+    assert mapping.dtype == torch.int32 and flags.dtype == torch.uint8 and mask.numel() >= mapping.numel()
+    rc = load().cdf_active_rows(_ptr(flags), _ptr(mapping), ctypes.c_int32(mapping.numel()), _ptr(mask), _ptr(idx),
+                                _ptr(n_sent), _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()), _stream())
+    _check("cdf_active_rows", rc)
+
+
+def cdf_relu_fwd(z, h):
+    assert z.dtype == h.dtype == torch.float32 and z.numel() == h.numel() and z.is_contiguous() and h.is_contiguous()
+    _check("cdf_relu_fwd", load().cdf_relu_fwd(_ptr(z), _ptr(h), ctypes.c_int64(z.numel()), _stream()))
 
 
 def cdf_eps_update(eps, acc, mean_acc, params=None):

@@ -192,6 +192,26 @@ __global__ __launch_bounds__(kRowsPerBlock) void compact_kernel(const uint8_t* _
   if (on) idx[base + __popcll(b & ((1ull << lane) - 1ull))] = row;
 }
 
+// mask[r] = flags[map[r]] != 0 for a block of kRowsPerBlock rows, plus the block's count.
+__global__ __launch_bounds__(kRowsPerBlock) void flag_mask_kernel(const uint8_t* __restrict__ flags,
+                                                                  const int* __restrict__ map, int n_rows,
+                                                                  uint8_t* __restrict__ mask,
+                                                                  int* __restrict__ block_counts) {
+  __shared__ int wcnt[kRowsPerBlock / 64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * kRowsPerBlock + threadIdx.x;
+  const bool on = row < n_rows && flags[map[row]] != 0;
+  if (row < n_rows) mask[row] = on ? 1 : 0;
+  const unsigned long long b = __ballot(on);
+  if (lane == 0) wcnt[wave] = __popcll(b);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int t = 0;
+    for (int w = 0; w < kRowsPerBlock / 64; ++w) t += wcnt[w];
+    block_counts[blockIdx.x] = t;
+  }
+}
+
 template <typename T, int EPV>
 static void launch_filter(const void* cur, const void* cached, int n_rows, int dim, int64_t ld, float eps,
                           cdf_norm norm, int glog, uint8_t* mask, int* counts, int nblocks, hipStream_t st) {
@@ -264,5 +284,31 @@ extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_r
   CDF_LAUNCH_CHECK("cdf_cache_filter/scan");
   { ProfScope ps(K_COMPACT, st); compact_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(mask, n_rows, offsets, idx); }
   CDF_LAUNCH_CHECK("cdf_cache_filter/compact");
+  return CDF_OK;
+}
+
+extern "C" int cdf_active_rows(const uint8_t* flags, const int32_t* map, int32_t n_rows, uint8_t* mask, int32_t* idx,
+                               int32_t* n_sent, void* ws, size_t ws_bytes, void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  CDF_REQUIRE(n_rows >= 0, "cdf_active_rows: negative row count");
+  CDF_REQUIRE(n_sent != nullptr, "cdf_active_rows: n_sent is null");
+  if (n_rows == 0) {
+    scan_kernel<<<1, 1024, 0, st>>>(nullptr, 0, nullptr, n_sent);
+    CDF_LAUNCH_CHECK("cdf_active_rows/scan");
+    return CDF_OK;
+  }
+  CDF_REQUIRE(flags && map && mask && idx, "cdf_active_rows: null pointer");
+  const int nblocks = static_cast<int>(ceil_div(n_rows, kRowsPerBlock));
+  if (!ws || ws_bytes < filter_workspace_bytes(n_rows) || !aligned(ws, 4))
+    CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_active_rows: workspace too small (%zu < %zu)", ws_bytes,
+             filter_workspace_bytes(n_rows));
+  int* counts = static_cast<int*>(ws);
+  int* offsets = counts + nblocks + 1;
+  flag_mask_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(flags, map, n_rows, mask, counts);
+  CDF_LAUNCH_CHECK("cdf_active_rows/mask");
+  scan_kernel<<<1, 1024, 0, st>>>(counts, nblocks, offsets, n_sent);
+  CDF_LAUNCH_CHECK("cdf_active_rows/scan");
+  compact_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(mask, n_rows, offsets, idx);
+  CDF_LAUNCH_CHECK("cdf_active_rows/compact");
   return CDF_OK;
 }

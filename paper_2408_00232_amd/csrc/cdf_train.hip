@@ -157,6 +157,21 @@ __global__ __launch_bounds__(256) void map_index_kernel(const int* __restrict__ 
   for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) out[i] = map[idx[i]];
 }
 
+__global__ __launch_bounds__(256) void mark_rows_kernel(const int* __restrict__ idx, const int* __restrict__ n_sent,
+                                                        int max_sent, const int* __restrict__ map, int offset,
+                                                        uint8_t* __restrict__ flags) {
+  int n = *n_sent;
+  n = n < max_sent ? n : max_sent;
+  for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x)
+    flags[(map ? map[idx[i]] : idx[i]) + offset] = 1;
+}
+
+__global__ __launch_bounds__(256) void relu_kernel(const float* __restrict__ z, float* __restrict__ h, int64_t count) {
+  for (int64_t i = blockIdx.x * static_cast<int64_t>(blockDim.x) + threadIdx.x; i < count;
+       i += static_cast<int64_t>(gridDim.x) * blockDim.x)
+    h[i] = fmaxf(z[i], 0.0f);
+}
+
 static unsigned grid_for(int64_t count) {
   const int64_t b = ceil_div(count, 256);
   return static_cast<unsigned>(b < 1 ? 1 : (b > 65536 ? 65536 : b));
@@ -243,6 +258,26 @@ extern "C" int cdf_map_index(const int32_t* idx, const int32_t* n_sent, int32_t 
   CDF_REQUIRE(idx && n_sent && map && out, "cdf_map_index: null pointer");
   map_index_kernel<<<grid_for(max_sent), 256, 0, static_cast<hipStream_t>(stream)>>>(idx, n_sent, max_sent, map, out);
   CDF_LAUNCH_CHECK("cdf_map_index");
+  return CDF_OK;
+}
+
+extern "C" int cdf_mark_rows(const int32_t* idx, const int32_t* n_sent, int32_t max_sent, const int32_t* map,
+                             int32_t offset, uint8_t* flags, void* stream) {
+  CDF_REQUIRE(max_sent >= 0, "cdf_mark_rows: negative capacity");
+  if (max_sent == 0) return CDF_OK;
+  CDF_REQUIRE(idx && n_sent && flags, "cdf_mark_rows: null pointer");
+  mark_rows_kernel<<<grid_for(max_sent), 256, 0, static_cast<hipStream_t>(stream)>>>(idx, n_sent, max_sent, map, offset,
+                                                                                     flags);
+  CDF_LAUNCH_CHECK("cdf_mark_rows");
+  return CDF_OK;
+}
+
+extern "C" int cdf_relu_fwd(const float* z, float* h, int64_t count, void* stream) {
+  CDF_REQUIRE(count >= 0, "cdf_relu_fwd: negative count");
+  if (count == 0) return CDF_OK;
+  CDF_REQUIRE(z && h, "cdf_relu_fwd: null pointer");
+  relu_kernel<<<grid_for(count), 256, 0, static_cast<hipStream_t>(stream)>>>(z, h, count);
+  CDF_LAUNCH_CHECK("cdf_relu_fwd");
   return CDF_OK;
 }
 

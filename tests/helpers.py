@@ -63,3 +63,11 @@ def oracle_parts(parts):
     from oracle import training
     return [training.Part(P.n_loc, P.n_halo, P.owned.cpu().numpy(), P.halo.cpu().numpy(), csr_np(P), csr_np(P, True))
             for P in parts]
+
+
+def oracle_vc_parts(parts):
+    """cdfgen vertex-cut partitions -> the oracle's records."""
+    from oracle import vc_training
+    return [vc_training.Part(P.n_master, P.n_mirror, P.vertices.numpy(),
+                             (P.rowptr.numpy(), P.colidx.numpy(), P.vals.numpy()),
+                             P.mirror_master_dev.numpy(), P.mirror_master_row.numpy()) for P in parts]

@@ -1,0 +1,133 @@
+"""Training in the vertex-cut framing (master / mirror replicas, Alg. 2 in full) on the device
+against the oracle's loop on the same seeded task and the same hashed vertex-cut."""
+import numpy as np
+import pytest
+import torch
+
+from cdfgen import configs, vertex_cut as vcut
+from helpers import assert_rows_close, oracle_vc_parts
+
+pytestmark = pytest.mark.gpu
+
+
+def _pair(w, oracle, p, **kw):
+    from oracle import vc_training
+    from paper_2408_00232_amd.vc_trainer import VcTrainer
+    g = configs.build_graph(w)
+    part = vcut.hashed_edge_cut(g, p, w.seed)
+    qname = kw.pop("qscheme", w.qscheme)
+    tr = VcTrainer(w, device="cuda:0", keep_inputs=True, qscheme=qname, edge_part=part, graph=g, p=p, **kw)
+    I = tr.inputs
+    qs = {"minmax": oracle.Q_MINMAX, "symmetric": oracle.Q_SYMMETRIC, "none": oracle.Q_NONE}[qname]
+    ref = vc_training.Trainer(oracle_vc_parts(tr.parts), w.layers(), I["x0"].numpy(), I["labels"].numpy(),
+                              I["train"].numpy(), [W.cpu().numpy() for W in tr.W], eps=tr.eps, lr=tr.lr,
+                              adaptive=tr.adaptive, qs=qs, bits=tr.bits)
+    return tr, ref
+
+
+@pytest.mark.parametrize("n,p", [(600, 3), (2048, 4)])
+def test_uncached_lossless_epochs_follow_the_oracle(oracle, n, p):
+    w = configs.shrink(configs.TINY, n) if n != configs.TINY.n_vertices else configs.TINY
+    tr, ref = _pair(w, oracle, p, eps0=0.0, adaptive=False, qscheme="none")
+    for t in range(4):
+        st, rs = tr.epoch(), ref.epoch()
+        if t == 0:
+            assert (st.gather, st.scatter, st.master_updates) == (rs["gather"], rs["scatter"], rs["master_updates"])
+        assert st.mirror_rows == rs["mirror_rows"]
+        assert abs(st.loss - rs["loss"]) <= 1e-5 * max(1.0, rs["loss"])
+        assert abs(st.train_acc - rs["train_acc"]) <= 2.0 / tr.n_train
+        assert_rows_close(tr.logits_by_vertex().numpy(), rs["logits"], rel=2e-4, frob=2e-5, what=f"logits epoch {t}")
+        for l in range(tr.L):
+            assert_rows_close(tr.dW[0][l].cpu().numpy(), rs["dW"][l], rel=5e-4, frob=5e-5, what=f"dW{l} epoch {t}")
+            np.testing.assert_allclose(tr.W[l].cpu().numpy(), ref.W[l], rtol=0, atol=1e-4)
+
+
+def test_first_epoch_with_cache_and_quantiser(oracle):
+    """Epoch 0 from identical (zero) caches: equal message counts in all three phases; values within a
+    few 8-bit code steps (the partial sums differ in their last bits between the two sides)."""
+    w = configs.shrink(configs.TINY, 900)
+    tr, ref = _pair(w, oracle, 4, eps0=0.05, adaptive=False)
+    st, rs = tr.epoch(), ref.epoch()
+    assert abs(st.gather - rs["gather"]) <= 2 and abs(st.scatter - rs["scatter"]) <= 4
+    assert abs(st.master_updates - rs["master_updates"]) <= 2
+    assert_rows_close(tr.logits_by_vertex().numpy(), rs["logits"], rel=2e-2, frob=2e-3, what="logits")
+    for l in range(tr.L):
+        assert_rows_close(tr.dW[0][l].cpu().numpy(), rs["dW"][l], rel=3e-2, frob=3e-3, what=f"dW{l}")
+
+
+def test_alg2_invariants_on_the_device(oracle):
+    """Loss-less messages, threshold 0.1, 8 epochs: every mirror's copy equals its master's total bit for
+    bit, the master's total equals the sum of the replicas' cached partial values, fewer messages than
+    mirror rows, and the loss falls."""
+    w = configs.shrink(configs.TINY, 1200)
+    tr, ref = _pair(w, oracle, 4, eps0=0.1, adaptive=False, qscheme="none", lr=0.02)
+    hist = [tr.epoch() for _ in range(8)]
+    verts = tr.vertices.numpy()
+    ism = tr.is_master.numpy()
+    for st in tr.zx + tr.dx[1:]:
+        tot, zc = st.tot.cpu().numpy(), st.zc.cpu().numpy()
+        total = np.zeros((tr.n, st.dim))
+        np.add.at(total, verts, zc.astype(np.float64))
+        by_vertex = np.zeros((tr.n, st.dim), np.float32)
+        by_vertex[verts[ism]] = tot[ism]
+        assert np.array_equal(tot[~ism], by_vertex[verts[~ism]])
+        scale = np.abs(total).max() + 1e-30
+        np.testing.assert_allclose(by_vertex, total, rtol=0, atol=3e-5 * scale)
+    assert hist[-1].loss < 0.9 * hist[0].loss
+    late = hist[2:]
+    assert sum(h.gather + h.scatter for h in late) < 0.9 * sum(2 * h.mirror_rows for h in late)
+
+
+def test_adaptive_run_with_the_ebv_partition_tracks_the_oracle(oracle):
+    """The library's own partitioner feeds both sides (its output is integer data checked edge by edge
+    against the partitioner oracle elsewhere). 8-bit messages, controller on, 15 epochs, loose bounds."""
+    from oracle import vc_training
+    from paper_2408_00232_amd.vc_trainer import VcTrainer
+    w = configs.TINY
+    tr = VcTrainer(w, device="cuda:0", keep_inputs=True, eps0=0.01, lr=0.02)
+    I = tr.inputs
+    ref = vc_training.Trainer(oracle_vc_parts(tr.parts), w.layers(), I["x0"].numpy(), I["labels"].numpy(),
+                              I["train"].numpy(), [W.cpu().numpy() for W in tr.W], eps=tr.eps, lr=tr.lr, adaptive=True,
+                              qs=oracle.Q_MINMAX, bits=tr.bits)
+    for t in range(15):
+        st, rs = tr.epoch(), ref.epoch()
+        assert abs(st.eps - rs["eps"]) <= 0.0101, (t, st.eps, rs["eps"])
+        assert abs(st.loss - rs["loss"]) <= 0.03 * max(1.0, rs["loss"]), (t, st.loss, rs["loss"])
+        assert abs(st.train_acc - rs["train_acc"]) <= 0.04
+        assert abs((st.gather + st.scatter) - (rs["gather"] + rs["scatter"])) <= 0.05 * 2 * st.mirror_rows
+    assert tr.history[-1].loss < 0.9 * tr.history[0].loss
+
+
+def test_mark_active_relu_kernels():
+    from paper_2408_00232_amd import binding as B
+    g = torch.Generator().manual_seed(4)
+    flags = torch.zeros(5000, dtype=torch.uint8, device="cuda")
+    idx = torch.randperm(3000, generator=g)[:700].to(torch.int32).cuda()
+    mp = torch.randint(0, 4000, (3000,), generator=g, dtype=torch.int32).cuda()
+    ns = torch.tensor([650], dtype=torch.int32, device="cuda")
+    B.cdf_mark_rows(idx, ns, mp, 1000, flags)
+    want = torch.zeros(5000, dtype=torch.uint8)
+    want[mp.cpu()[idx[:650].cpu().long()].long() + 1000] = 1
+    assert torch.equal(flags.cpu(), want)
+    flags.zero_()
+    B.cdf_mark_rows(idx, ns, None, 7, flags)
+    want.zero_()
+    want[idx[:650].cpu().long() + 7] = 1
+    assert torch.equal(flags.cpu(), want)
+    # mirrors of active vertices: ascending list of rows whose master flag is set
+    mm = torch.randint(0, 5000, (1777,), generator=g, dtype=torch.int32).cuda()
+    mask = torch.zeros(1777, dtype=torch.uint8, device="cuda")
+    out = torch.full((1777,), -1, dtype=torch.int32, device="cuda")
+    n = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = torch.zeros(B.cdf_workspace_bytes(1777, 8, 0), dtype=torch.uint8, device="cuda")
+    B.cdf_active_rows(flags, mm, mask, out, n, ws)
+    on = want[mm.cpu().long()] != 0
+    exp = torch.nonzero(on).flatten().to(torch.int32)
+    assert int(n.item()) == exp.numel() and torch.equal(out[:exp.numel()].cpu(), exp)
+    assert torch.equal(mask.cpu(), on.to(torch.uint8))
+    B.cdf_active_rows(flags, mm[:0], mask, out, n, ws)
+    assert int(n.item()) == 0
+    z = torch.randn(1000, 37, generator=g).cuda()
+    h = torch.empty_like(z)
+    B.cdf_relu_fwd(z, h)
+    assert torch.equal(h.cpu(), torch.clamp_min(z.cpu(), 0))

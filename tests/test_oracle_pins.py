@@ -750,3 +750,85 @@ def test_training_loop_cache_reduces_messages_and_still_learns(oracle):
     # staleness of the reader's copy of layer-1 inputs after the last epoch: <= eps * |cached row|
     for P, xf, c in zip(tr.parts, tr.xfull, tr.cache):
         np.testing.assert_allclose(xf[1][P.n_loc:], c[1], rtol=0, atol=1e-5)   # reader copy == sender cache
+
+
+# --------------------------------------------------------------------------
+# The paper's own framing: vertex-cut, master / mirror replicas, Alg. 2 in full
+# --------------------------------------------------------------------------
+def _vc_task(n, seed, p, classes, f0, f1, signal=0.5):
+    from cdfgen import labels as labelgen, vertex_cut as vcut
+    w, g = small_graph(n, seed=seed)
+    y = labelgen.planted_labels(g, classes, seed)
+    X = labelgen.planted_features(y, f0, seed, signal=signal).numpy()
+    tm = labelgen.train_mask(g.n, seed).numpy()
+    Ws = [features.glorot(seed, 70, f0, f1).numpy(), features.glorot(seed, 71, f1, classes).numpy()]
+    part = vcut.hashed_edge_cut(g, p, seed)
+    parts = vcut.extract_vertex_cut(g, part, vcut.choose_masters(g, part, p), p)
+    return g, y.numpy(), X, tm, Ws, parts
+
+
+def test_vertex_cut_blocks_sum_to_the_normalised_adjacency():
+    from cdfgen import vertex_cut as vcut
+    w, g = small_graph(150, seed=9)
+    part = vcut.hashed_edge_cut(g, 3, 9)
+    master = vcut.choose_masters(g, part, 3)
+    parts = vcut.extract_vertex_cut(g, part, master, 3)
+    A = np.zeros((g.n, g.n))
+    owners = np.zeros(g.n, int)
+    for i, P in enumerate(parts):
+        v = P.vertices.numpy()
+        A[np.ix_(v, v)] += csr_dense(P.rowptr.numpy(), P.colidx.numpy(), P.vals.numpy(), P.n)
+        owners[v[:P.n_master]] += 1
+        assert (master[P.vertices[:P.n_master]] == i).all() and (master[P.vertices[P.n_master:]] != i).all()
+        md, mr = P.mirror_master_dev.numpy(), P.mirror_master_row.numpy()
+        for k in range(P.n_mirror):                        # the mirror's record points at the same vertex
+            assert parts[md[k]].vertices[mr[k]] == P.vertices[P.n_master + k] and mr[k] < parts[md[k]].n_master
+    np.testing.assert_allclose(A, dense_norm_adj(g), atol=1e-7)
+    assert (owners == 1).all()                             # every vertex has exactly one master
+
+
+def test_vertex_cut_training_without_cache_equals_full_graph_training(oracle):
+    """Sec. 3.2's claim: after gather and scatter the replicas hold what sequential training would.
+    Threshold 0 and loss-less messages, four epochs against dense float64 training."""
+    from helpers import oracle_vc_parts
+    from oracle import vc_training
+    g, y, X, tm, Ws, parts = _vc_task(240, 5, 3, 5, 12, 9)
+    tr = vc_training.Trainer(oracle_vc_parts(parts), [(12, 9), (9, 5)], X, y, tm, Ws, eps=0.0, lr=0.01, adaptive=False,
+                             qs=oracle.Q_NONE)
+    ref = _dense_gcn_training(dense_norm_adj(g), X.astype(np.float64), y, tm, Ws, 0.01, 4)
+    for t in range(4):
+        st = tr.epoch()
+        assert abs(st["loss"] - ref[t]["loss"]) < 2e-6 * max(1.0, ref[t]["loss"])
+        assert_rows_close(st["logits"], ref[t]["logits"], rel=2e-4, frob=2e-5, what=f"logits {t}")
+        for k in range(2):
+            assert_rows_close(st["dW"][k], ref[t]["dW"][k], rel=5e-4, frob=5e-5, what=f"dW{k} epoch {t}")
+            np.testing.assert_allclose(tr.W[k], ref[t]["W"][k], rtol=0, atol=2e-4)
+
+
+def test_alg2_invariants_with_a_positive_threshold(oracle):
+    """With loss-less messages and threshold 0.1, after every exchange: (a) the master's cached total
+    equals the sum of the cached partial values of all replicas of the vertex; (b) every mirror's copy
+    equals its master's total (any change activates the vertex and is scattered); and fewer rows
+    travel than with threshold 0."""
+    from helpers import oracle_vc_parts
+    from oracle import vc_training
+    g, y, X, tm, Ws, parts = _vc_task(240, 6, 3, 4, 10, 8, signal=0.6)
+    oparts = oracle_vc_parts(parts)
+    sent = {}
+    for eps in (0.0, 0.1):
+        tr = vc_training.Trainer(oparts, [(10, 8), (8, 4)], X, y, tm, Ws, eps=eps, lr=0.02, adaptive=False,
+                                 qs=oracle.Q_NONE)
+        hist = [tr.epoch() for _ in range(10)]
+        sent[eps] = sum(h["gather"] + h["scatter"] for h in hist)
+        for st in tr.zs + tr.ds[1:]:
+            dim = st.zc[0].shape[1]
+            total = np.zeros((g.n, dim))
+            for P, zc in zip(oparts, st.zc):
+                np.add.at(total, P.vertices, zc.astype(np.float64))
+            for P, tot in zip(oparts, st.tot):
+                scale = np.abs(total[P.vertices]).max() + 1e-30
+                np.testing.assert_allclose(tot[:P.n_master], total[P.vertices[:P.n_master]], rtol=0, atol=3e-5 * scale)
+                for k in range(P.n_mirror):
+                    assert np.array_equal(tot[P.n_master + k], oparts[P.mdev[k]].tot_row(st, P.mrow[k]))
+        assert hist[-1]["loss"] < 0.9 * hist[0]["loss"]
+    assert sent[0.1] < 0.8 * sent[0.0]
