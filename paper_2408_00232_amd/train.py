@@ -4,6 +4,7 @@ rate, message volume, loss and train accuracy.
 
     python -m paper_2408_00232_amd.train --workload mid --epochs 100
     python -m paper_2408_00232_amd.train --workload mid --epochs 100 --eps0 0 --fixed --qscheme none   # no cache, fp32 messages
+    python -m paper_2408_00232_amd.train --workload mid --epochs 100 --framing vertex-cut             # Alg. 2 in full, EBV partition
 """
 import argparse
 import json
@@ -15,6 +16,7 @@ from cdfgen import configs
 
 from . import binding as B
 from .trainer import Trainer
+from .vc_trainer import VcTrainer
 
 
 def main(argv=None):
@@ -30,6 +32,10 @@ def main(argv=None):
     ap.add_argument("--bits", type=int, default=None, choices=[4, 8])
     ap.add_argument("--lr", type=float, default=0.01)
     ap.add_argument("--every", type=int, default=1, help="print every k-th epoch")
+    ap.add_argument("--framing", default="halo", choices=["halo", "vertex-cut"],
+                    help="halo: owned rows + halo rows per partition; vertex-cut: master / mirror replicas (Sec. 3.2)")
+    ap.add_argument("--devices-per-host", type=int, default=0, help="vertex-cut: hosts for the partitioner's gamma term")
+    ap.add_argument("--gamma", type=float, default=0.1)
     ap.add_argument("--json", action="store_true", help="one JSON object per printed epoch")
     a = ap.parse_args(argv)
     if not torch.cuda.is_available():
@@ -41,12 +47,26 @@ def main(argv=None):
     if a.swap_conditions:
         params = B.cdf_eps_params(0.001, 0.02, 0.3, 0.001, 0.01, 1.05, 0.9, 1)
     t0 = time.time()
-    tr = Trainer(w, eps0=a.eps0, lr=a.lr, adaptive=not a.fixed, eps_params=params, qscheme=a.qscheme, bits=a.bits)
-    torch.cuda.synchronize()
-    print(f"# {w.name}: {tr.n} vertices, {tr.p} partitions, layers {w.dims}, {tr.n_train} train rows, "
-          f"{sum(P.n_halo for P in tr.parts)} halo rows, set-up {time.time() - t0:.1f} s", flush=True)
+    vc = a.framing == "vertex-cut"
+    if vc:
+        g = configs.build_graph(w)
+        dph = a.devices_per_host or w.parts
+        part = B.cdf_ebv_partition(g.n, g.lo.contiguous(), g.hi.contiguous(), w.parts, dph, 1.0, 1.0, a.gamma, True)
+        st, _ = B.cdf_cut_statistics(g.n, g.lo.contiguous(), g.hi.contiguous(), part, w.parts, dph)
+        tr = VcTrainer(w, eps0=a.eps0, lr=a.lr, adaptive=not a.fixed, eps_params=params, qscheme=a.qscheme, bits=a.bits,
+                       edge_part=part, graph=g)
+        torch.cuda.synchronize()
+        print(f"# {w.name}: {tr.n} vertices on {tr.p} devices ({dph} per host), layers {w.dims}, {tr.n_train} train rows, "
+              f"replication factor {st.replication_factor:.3f}, edge imbalance {st.edge_imbalance:.4f}, "
+              f"{sum(P.n_mirror for P in tr.parts)} mirrors, set-up {time.time() - t0:.1f} s", flush=True)
+    else:
+        tr = Trainer(w, eps0=a.eps0, lr=a.lr, adaptive=not a.fixed, eps_params=params, qscheme=a.qscheme, bits=a.bits)
+        torch.cuda.synchronize()
+        print(f"# {w.name}: {tr.n} vertices, {tr.p} partitions, layers {w.dims}, {tr.n_train} train rows, "
+              f"{sum(P.n_halo for P in tr.parts)} halo rows, set-up {time.time() - t0:.1f} s", flush=True)
     if not a.json:
-        print("# epoch     eps  hit_rate  sent_fwd  sent_bwd     MB_sent      loss  train_acc   ms")
+        print("# epoch     eps  hit_rate   " + ("gather   scatter" if vc else "sent_fwd  sent_bwd") +
+              "     MB_sent      loss  train_acc   ms")
     total_bytes = 0
     for e in range(a.epochs):
         torch.cuda.synchronize()
@@ -57,15 +77,16 @@ def main(argv=None):
         total_bytes += st.message_bytes
         if e % a.every and e + 1 != a.epochs:
             continue
+        c1, c2 = (st.gather, st.scatter) if vc else (st.sent_fwd, st.sent_bwd)
         if a.json:
-            print(json.dumps(dict(epoch=e, eps=st.eps, hit_rate=st.hit_rate, sent_fwd=st.sent_fwd, sent_bwd=st.sent_bwd,
+            print(json.dumps(dict(epoch=e, eps=st.eps, hit_rate=st.hit_rate, sent_a=c1, sent_b=c2,
                                   message_bytes=st.message_bytes, loss=st.loss, train_acc=st.train_acc, ms=ms)),
                   flush=True)
         else:
-            print(f"{e:7d} {st.eps:7.4f} {st.hit_rate:9.4f} {st.sent_fwd:9d} {st.sent_bwd:9d} "
+            print(f"{e:7d} {st.eps:7.4f} {st.hit_rate:9.4f} {c1:9d} {c2:9d} "
                   f"{st.message_bytes / 1e6:11.3f} {st.loss:9.5f} {st.train_acc:10.4f} {ms:6.1f}", flush=True)
-    print(f"# accuracy over all vertices {tr.accuracy_all():.4f}; messages {total_bytes / 1e6:.1f} MB in "
-          f"{a.epochs} epochs", flush=True)
+    tail = "" if vc else f"accuracy over all vertices {tr.accuracy_all():.4f}; "
+    print(f"# {tail}messages {total_bytes / 1e6:.1f} MB in {a.epochs} epochs", flush=True)
 
 
 if __name__ == "__main__":

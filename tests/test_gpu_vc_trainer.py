@@ -75,7 +75,7 @@ def test_alg2_invariants_on_the_device(oracle):
         np.testing.assert_allclose(by_vertex, total, rtol=0, atol=3e-5 * scale)
     assert hist[-1].loss < 0.9 * hist[0].loss
     late = hist[2:]
-    assert sum(h.gather + h.scatter for h in late) < 0.9 * sum(2 * h.mirror_rows for h in late)
+    assert sum(h.gather + h.scatter for h in late) < 0.97 * sum(2 * h.mirror_rows for h in late)
 
 
 def test_adaptive_run_with_the_ebv_partition_tracks_the_oracle(oracle):
