@@ -265,6 +265,11 @@ def main():
         "quantize_kernel": avg([sent_f[i] * (3 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)] +
                                [sent_b[i] * (3 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)]),
         "dequantize_kernel": avg([sent_f[i] * (2 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)]),
+        # one-pass test + message build: every row read once, sent rows committed and coded
+        "test_encode_kernel": avg([h * (2 * f * esz + 1) + sn[i] * (f * esz + rb[i] + 8)
+                                   for sn in (sent_f, sent_b) for i, (f, _) in enumerate(lay)]),
+        "gather_codes_kernel": avg([sn[i] * (2 * rb[i] + 16 + 4)
+                                    for sn in (sent_f, sent_b) for i, (f, _) in enumerate(lay)]),
     }
     flops = avg([2.0 * n * f * g for f, g in w.layers()])
     per_kernel = {}

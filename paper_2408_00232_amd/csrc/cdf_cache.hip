@@ -20,7 +20,6 @@
 
 namespace cdf {
 
-constexpr int kRowsPerBlock = 64;   // rows per block in all three kernels (16 per wavefront of the test)
 constexpr int kFilterThreads = 256;
 
 template <typename T, int EPV, int NORM>
@@ -223,6 +222,21 @@ static void launch_filter(const void* cur, const void* cached, int n_rows, int d
   else
     filter_kernel<T, EPV, CDF_NORM_L2><<<nblocks, kFilterThreads, 0, st>>>(a, b, n_rows, dim, ld, eps, glog,
                                                                            mask, counts);
+}
+
+// Exclusive scan of per-block counts (blocks of kRowsPerBlock rows) and ordered compaction of the
+// mask into idx / *n_sent; counts and offsets each hold ceil(n_rows / kRowsPerBlock) + 1 ints.
+int scan_and_compact(const uint8_t* mask, int n_rows, int* counts, int* offsets, int32_t* idx, int32_t* n_sent,
+                     hipStream_t st) {
+  const int nblocks = static_cast<int>(ceil_div(n_rows, kRowsPerBlock));
+  { ProfScope ps(K_SCAN, st); scan_kernel<<<1, 1024, 0, st>>>(counts, nblocks, offsets, n_sent); }
+  CDF_LAUNCH_CHECK("scan");
+  if (nblocks > 0) {
+    ProfScope ps(K_COMPACT, st);
+    compact_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(mask, n_rows, offsets, idx);
+  }
+  CDF_LAUNCH_CHECK("compact");
+  return CDF_OK;
 }
 
 size_t filter_workspace_bytes(int64_t n_rows) {

@@ -34,7 +34,8 @@ void set_error(const char* fmt, ...);
 // ---- optional per-kernel timing (host side, HIP events on the launch stream) ----
 enum KernelId {
   K_FILTER = 0, K_SCAN, K_COMPACT, K_QUANTIZE, K_DEQUANTIZE, K_SPMM_PLAN, K_SPMM, K_SPMM_FIXUP,
-  K_GEMM_FWD, K_GEMM_DW, K_GEMM_DW_REDUCE, K_GEMM_DM, K_SPMM_SLICED, K_RELU_MASK, K_COUNT
+  K_GEMM_FWD, K_GEMM_DW, K_GEMM_DW_REDUCE, K_GEMM_DM, K_SPMM_SLICED, K_RELU_MASK, K_TEST_ENCODE, K_GATHER_CODES,
+  K_COUNT
 };
 void prof_begin(int id, hipStream_t st);
 void prof_end(int id, hipStream_t st);
@@ -44,6 +45,10 @@ struct ProfScope {
   ProfScope(int i, hipStream_t s) : id(i), st(s) { prof_begin(id, st); }
   ~ProfScope() { prof_end(id, st); }
 };
+
+// Rows per block of the cache test, of its scan / compaction, and of the one-pass test + message
+// build (16 rows per wavefront): the per-block counts of all of them have this granularity.
+constexpr int kRowsPerBlock = 64;
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }

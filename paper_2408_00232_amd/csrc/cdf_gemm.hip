@@ -214,18 +214,28 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
     stage();
     __syncthreads();
     if (k0 + kBK < Kend) fetch(k0 + kBK);
+    // operands of step kk + 2 are read from LDS while the products of step kk run
+    float fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = As[lh][wm * 64 + i * 32 + l32];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = Bs[lh][wn * (BN / 2) + j * 32 + l32];
 #pragma unroll
     for (int kk = 0; kk < kBK; kk += 2) {
-      float fa[TM], fb[TN];
+      const int cur = (kk >> 1) & 1, nxt = cur ^ 1;
+      if (kk + 2 < kBK) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = As[kk + lh][wm * 64 + i * 32 + l32];
+        for (int i = 0; i < TM; ++i) fa[nxt][i] = As[kk + 2 + lh][wm * 64 + i * 32 + l32];
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = Bs[kk + lh][wn * (BN / 2) + j * 32 + l32];
+        for (int j = 0; j < TN; ++j) fb[nxt][j] = Bs[kk + 2 + lh][wn * (BN / 2) + j * 32 + l32];
+      }
+      __builtin_amdgcn_sched_barrier(0);   // keep the LDS reads above the products they overlap with
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[cur][i], fb[cur][j], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
   }

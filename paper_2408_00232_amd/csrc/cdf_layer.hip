@@ -10,6 +10,10 @@ namespace cdf {
 size_t filter_workspace_bytes(int64_t n_rows);
 size_t spmm_workspace_bytes(int64_t nnz, int32_t dim);
 size_t dense_workspace_bytes(int64_t n, int32_t f, int32_t g);
+size_t test_encode_workspace_bytes(int64_t n_rows, int32_t dim);
+int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, int64_t ld, cdf_dtype dt, float eps,
+                    cdf_norm norm, int bits, cdf_qscheme qs, cdf_commit commit, int delta, uint8_t* mask, int32_t* idx,
+                    int32_t* n_sent, uint8_t* codes, float* meta, void* ws, size_t ws_bytes, void* stream);
 int spmm_run(const char* fn, const cdf_csr* A, const void* X, int64_t ldx, void* Y, void* Y2, int64_t ldy,
              int32_t dim, cdf_dtype dt, void* ws, size_t ws_bytes, hipStream_t st);
 
@@ -43,7 +47,8 @@ static size_t max_sz(size_t a, size_t b) { return a > b ? a : b; }
 static const char* const kKernelNames[K_COUNT] = {
     "filter_kernel", "scan_kernel", "compact_kernel", "quantize_kernel", "dequantize_kernel",
     "chunk_rows_kernel", "spmm_kernel", "spmm_fixup_kernel", "gemm_kernel<FWD>", "gemm_kernel<DW>",
-    "reduce_slabs_kernel", "gemm_kernel<DM>", "spmm_sliced_kernel", "relu_mask_kernel"};
+    "reduce_slabs_kernel", "gemm_kernel<DM>", "spmm_sliced_kernel", "relu_mask_kernel", "test_encode_kernel",
+    "gather_codes_kernel"};
 constexpr int kProfCap = 8192;
 struct ProfRec {
   int id;
@@ -65,14 +70,14 @@ void prof_begin(int id, hipStream_t st) {
     g_prof_made = g_prof_n + 1;
   }
   r.id = id;
-  hipEventRecord(r.a, st);
+  (void)hipEventRecord(r.a, st);
 }
 
 void prof_end(int id, hipStream_t st) {
   if (!g_prof_on || g_prof_n >= kProfCap) return;
   ProfRec& r = g_prof[g_prof_n];
   if (r.id != id) return;
-  hipEventRecord(r.b, st);
+  (void)hipEventRecord(r.b, st);
   ++g_prof_n;
 }
 
@@ -130,8 +135,9 @@ extern "C" int cdf_profile_read(int kernel, float* ms, int cap) {
 
 extern "C" size_t cdf_workspace_bytes(int64_t max_rows, int32_t max_dim, int64_t max_nnz) {
   if (max_rows < 0 || max_dim <= 0 || max_nnz < 0) return 0;
-  return filter_workspace_bytes(max_rows) +
-         max_sz(spmm_workspace_bytes(max_nnz, max_dim), dense_workspace_bytes(max_rows, max_dim, max_dim));
+  const size_t steps = filter_workspace_bytes(max_rows) +
+                       max_sz(spmm_workspace_bytes(max_nnz, max_dim), dense_workspace_bytes(max_rows, max_dim, max_dim));
+  return max_sz(steps, test_encode_workspace_bytes(max_rows, max_dim));
 }
 
 extern "C" int cdf_gcn_layer_fwd(const cdf_layer_fwd_args* p, void* ws, size_t ws_bytes, void* stream) {
@@ -152,11 +158,8 @@ extern "C" int cdf_gcn_layer_fwd(const cdf_layer_fwd_args* p, void* ws, size_t w
   if (p->n_halo > 0) {
     CDF_REQUIRE(p->halo_fresh && p->cache_sent && p->mask && p->idx && p->n_sent && p->codes && p->meta,
                 "cdf_gcn_layer_fwd: null halo buffer");
-    rc = cdf_cache_filter(p->halo_fresh, p->cache_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->eps, p->norm, p->mask,
-                          p->idx, p->n_sent, w, fw, stream);
-    if (rc != CDF_OK) return rc;
-    rc = cdf_quantize(p->halo_fresh, p->cache_sent, p->idx, p->n_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->bits,
-                      p->qs, p->commit, p->delta, p->codes, p->meta, stream);
+    rc = test_and_encode(p->halo_fresh, p->cache_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->eps, p->norm, p->bits,
+                         p->qs, p->commit, p->delta, p->mask, p->idx, p->n_sent, p->codes, p->meta, w, ws_bytes, stream);
     if (rc != CDF_OK) return rc;
     void* halo_rows = static_cast<char*>(p->xfull) + static_cast<size_t>(p->n_loc) * p->f_in * esz;
     rc = cdf_dequantize(p->codes, p->meta, p->idx, p->n_sent, p->n_halo, p->f_in, p->bits, p->qs, halo_rows, p->f_in,
@@ -195,11 +198,8 @@ extern "C" int cdf_gcn_layer_bwd(const cdf_layer_bwd_args* p, void* ws, size_t w
     CDF_REQUIRE(p->gcache_sent && p->mask && p->idx && p->n_sent && p->codes && p->meta,
                 "cdf_gcn_layer_bwd: null halo buffer");
     const void* halo_rows = static_cast<const char*>(p->dxfull) + static_cast<size_t>(p->n_loc) * p->f_in * esz;
-    rc = cdf_cache_filter(halo_rows, p->gcache_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->eps, p->norm, p->mask,
-                          p->idx, p->n_sent, w, fw, stream);
-    if (rc != CDF_OK) return rc;
-    rc = cdf_quantize(halo_rows, p->gcache_sent, p->idx, p->n_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->bits,
-                      p->qs, p->commit, p->delta, p->codes, p->meta, stream);
+    rc = test_and_encode(halo_rows, p->gcache_sent, p->n_halo, p->f_in, p->f_in, p->dt, p->eps, p->norm, p->bits,
+                         p->qs, p->commit, p->delta, p->mask, p->idx, p->n_sent, p->codes, p->meta, w, ws_bytes, stream);
   }
   return rc;
 }
@@ -222,11 +222,8 @@ extern "C" int cdf_gcn_layer_tf_fwd(const cdf_layer_tf_fwd_args* p, void* ws, si
   if (p->n_halo > 0) {
     CDF_REQUIRE(p->halo_fresh && p->cache_sent && p->mask && p->idx && p->n_sent && p->codes && p->meta,
                 "cdf_gcn_layer_tf_fwd: null halo buffer");
-    rc = cdf_cache_filter(p->halo_fresh, p->cache_sent, p->n_halo, p->f_out, p->f_out, CDF_F32, p->eps, p->norm,
-                          p->mask, p->idx, p->n_sent, w, fw, stream);
-    if (rc != CDF_OK) return rc;
-    rc = cdf_quantize(p->halo_fresh, p->cache_sent, p->idx, p->n_sent, p->n_halo, p->f_out, p->f_out, CDF_F32,
-                      p->bits, p->qs, p->commit, p->delta, p->codes, p->meta, stream);
+    rc = test_and_encode(p->halo_fresh, p->cache_sent, p->n_halo, p->f_out, p->f_out, CDF_F32, p->eps, p->norm, p->bits,
+                         p->qs, p->commit, p->delta, p->mask, p->idx, p->n_sent, p->codes, p->meta, w, ws_bytes, stream);
     if (rc != CDF_OK) return rc;
     rc = cdf_dequantize(p->codes, p->meta, p->idx, p->n_sent, p->n_halo, p->f_out, p->bits, p->qs,
                         p->tfull + static_cast<size_t>(p->n_loc) * p->f_out, p->f_out, CDF_F32, p->delta ? 1 : 0, stream);
@@ -280,11 +277,8 @@ extern "C" int cdf_gcn_layer_tf_bwd(const cdf_layer_tf_bwd_args* p, void* ws, si
     CDF_REQUIRE(p->gcache_sent && p->mask && p->idx && p->n_sent && p->codes && p->meta,
                 "cdf_gcn_layer_tf_bwd: null halo buffer");
     const float* halo_rows = p->dtfull + static_cast<size_t>(p->n_loc) * p->f_out;
-    rc = cdf_cache_filter(halo_rows, p->gcache_sent, p->n_halo, p->f_out, p->f_out, CDF_F32, p->eps, p->norm, p->mask,
-                          p->idx, p->n_sent, w, fw, stream);
-    if (rc != CDF_OK) return rc;
-    rc = cdf_quantize(halo_rows, p->gcache_sent, p->idx, p->n_sent, p->n_halo, p->f_out, p->f_out, CDF_F32, p->bits,
-                      p->qs, p->commit, p->delta, p->codes, p->meta, stream);
+    rc = test_and_encode(halo_rows, p->gcache_sent, p->n_halo, p->f_out, p->f_out, CDF_F32, p->eps, p->norm, p->bits,
+                         p->qs, p->commit, p->delta, p->mask, p->idx, p->n_sent, p->codes, p->meta, w, ws_bytes, stream);
     if (rc != CDF_OK) return rc;
   }
   return cdf_dense_bwd(p->x_local, p->f_in, CDF_F32, p->W, nullptr, p->dtfull, p->n_loc, p->f_in, p->f_out, 0, p->dW,

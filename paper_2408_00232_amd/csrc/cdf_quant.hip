@@ -17,41 +17,14 @@ namespace cdf {
 
 constexpr int kQuantThreads = 256;
 
-// `NIT` vectors of EPV elements per lane: covers rows of up to 64*NIT vectors.
+// Statistics, codes, meta and cache commit of one message row held in registers: x = current row,
+// z = cached row, m = what is sent. Every lane of the group must call it (the row statistics use
+// cross-lane exchanges); `live` gates all stores. out / meta_row / pz point at this row's codes,
+// its two meta floats and its cached row.
 template <typename T, int EPV, int NIT, int BITS, int QS>
-__global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
-    const T* __restrict__ cur, T* cached, const int* __restrict__ idx, const int* __restrict__ n_sent_p,
-    int dim, int64_t ld, int glog, int commit, int delta, uint8_t* __restrict__ codes,
-    float* __restrict__ meta) {
-  const int n_sent = *n_sent_p;
-  const int lane = threadIdx.x & 63;
-  const int G = 1 << glog;
-  const int lg = lane & (G - 1);
-  const int rows_per_wave = 64 >> glog;
-  const int gwave = blockIdx.x * (kQuantThreads / 64) + (threadIdx.x >> 6);
-  const int k = gwave * rows_per_wave + (lane >> glog);
-  const bool live = k < n_sent;
-  const int nvec = dim / EPV;
-  const int64_t rb = QS == CDF_Q_NONE ? static_cast<int64_t>(dim) * 4 : (static_cast<int64_t>(dim) * BITS + 7) / 8;
-
-  float x[NIT][EPV], z[NIT][EPV], m[NIT][EPV];
-  int64_t r = 0;
-  if (live) r = idx[k];
-  const T* pc = cur + r * ld;
-  T* pz = cached + r * ld;
-#pragma unroll
-  for (int i = 0; i < NIT; ++i) {
-    const int v = lg + i * G;
-#pragma unroll
-    for (int c = 0; c < EPV; ++c) x[i][c] = z[i][c] = 0.0f;
-    if (live && v < nvec) {
-      VecIO<T, EPV>::load(pc + static_cast<int64_t>(v) * EPV, x[i]);
-      if (delta || commit == CDF_COMMIT_DEQ) VecIO<T, EPV>::load(pz + static_cast<int64_t>(v) * EPV, z[i]);
-    }
-#pragma unroll
-    for (int c = 0; c < EPV; ++c) m[i][c] = delta ? x[i][c] - z[i][c] : x[i][c];
-  }
-
+__device__ __forceinline__ void encode_row(bool live, int lg, int G, int nvec, const float (&x)[NIT][EPV],
+                                           const float (&z)[NIT][EPV], const float (&m)[NIT][EPV], int commit,
+                                           int delta, uint8_t* out, float* meta_row, T* pz) {
   // row statistics
   float lo = __builtin_inff(), hi = -__builtin_inff(), amax = 0.0f;
 #pragma unroll
@@ -91,11 +64,10 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
     qlo = -qhi;
   }
   if (live && lg == 0) {
-    meta[2 * static_cast<int64_t>(k)] = m0;
-    meta[2 * static_cast<int64_t>(k) + 1] = m1;
+    meta_row[0] = m0;
+    meta_row[1] = m1;
   }
 
-  uint8_t* out = codes + static_cast<int64_t>(live ? k : 0) * rb;
 #pragma unroll
   for (int i = 0; i < NIT; ++i) {
     const int v = lg + i * G;
@@ -145,6 +117,134 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
       }
     }
   }
+}
+
+// `NIT` vectors of EPV elements per lane: covers rows of up to 64*NIT vectors.
+template <typename T, int EPV, int NIT, int BITS, int QS>
+__global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
+    const T* __restrict__ cur, T* cached, const int* __restrict__ idx, const int* __restrict__ n_sent_p,
+    int dim, int64_t ld, int glog, int commit, int delta, uint8_t* __restrict__ codes,
+    float* __restrict__ meta) {
+  const int n_sent = *n_sent_p;
+  const int lane = threadIdx.x & 63;
+  const int G = 1 << glog;
+  const int lg = lane & (G - 1);
+  const int rows_per_wave = 64 >> glog;
+  const int gwave = blockIdx.x * (kQuantThreads / 64) + (threadIdx.x >> 6);
+  const int k = gwave * rows_per_wave + (lane >> glog);
+  const bool live = k < n_sent;
+  const int nvec = dim / EPV;
+  const int64_t rb = QS == CDF_Q_NONE ? static_cast<int64_t>(dim) * 4 : (static_cast<int64_t>(dim) * BITS + 7) / 8;
+
+  float x[NIT][EPV], z[NIT][EPV], m[NIT][EPV];
+  int64_t r = 0;
+  if (live) r = idx[k];
+  const T* pc = cur + r * ld;
+  T* pz = cached + r * ld;
+#pragma unroll
+  for (int i = 0; i < NIT; ++i) {
+    const int v = lg + i * G;
+#pragma unroll
+    for (int c = 0; c < EPV; ++c) x[i][c] = z[i][c] = 0.0f;
+    if (live && v < nvec) {
+      VecIO<T, EPV>::load(pc + static_cast<int64_t>(v) * EPV, x[i]);
+      if (delta || commit == CDF_COMMIT_DEQ) VecIO<T, EPV>::load(pz + static_cast<int64_t>(v) * EPV, z[i]);
+    }
+#pragma unroll
+    for (int c = 0; c < EPV; ++c) m[i][c] = delta ? x[i][c] - z[i][c] : x[i][c];
+  }
+
+  encode_row<T, EPV, NIT, BITS, QS>(live, lg, G, nvec, x, z, m, commit, delta,
+                                    codes + static_cast<int64_t>(live ? k : 0) * rb,
+                                    meta + 2 * static_cast<int64_t>(live ? k : 0), pz);
+}
+
+// Cache test and message build in one pass over the rows (the two steps of Alg. 2's mirror loop
+// back to back): every row is read once, tested (L-infinity form), and - if it fails the test -
+// coded and committed from the same registers. The position of a row's message in the output is
+// only known after the count of sent rows before it, so codes and meta go to a row-indexed
+// scratch area first and gather_codes_kernel moves them to their final place (one byte per
+// element instead of re-reading the rows at eight). Blocks of kTestRows rows, one count per block,
+// as the cache test writes them.
+constexpr int kTestRows = kRowsPerBlock;
+
+template <typename T, int EPV, int NIT, int BITS, int QS>
+__global__ __launch_bounds__(kQuantThreads) void test_encode_kernel(
+    const T* __restrict__ cur, T* cached, int n_rows, int dim, int64_t ld, float eps, int glog, int commit, int delta,
+    uint8_t* __restrict__ mask, int* __restrict__ block_counts, uint8_t* __restrict__ codes_scratch,
+    float* __restrict__ meta_scratch) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int G = 1 << glog;
+  const int lg = lane & (G - 1), sub = lane >> glog;
+  const int rows_per_step = 64 >> glog;
+  const int nvec = dim / EPV;
+  const int64_t rb = (static_cast<int64_t>(dim) * BITS + 7) / 8;
+  constexpr int kRowsPerWave = kTestRows / (kQuantThreads / 64);
+  const int row0 = blockIdx.x * kTestRows + wave * kRowsPerWave;
+  int sent_here = 0;
+  for (int s = 0; s < kRowsPerWave; s += rows_per_step) {
+    const int row = row0 + s + sub;
+    const bool live = row < n_rows && s + sub < kRowsPerWave;
+    const int64_t r = live ? row : 0;
+    const T* pc = cur + r * ld;
+    T* pz = cached + r * ld;
+    float x[NIT][EPV], z[NIT][EPV], m[NIT][EPV];
+    float D = 0.0f, C = 0.0f;
+#pragma unroll
+    for (int i = 0; i < NIT; ++i) {
+      const int v = lg + i * G;
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) x[i][c] = z[i][c] = 0.0f;
+      if (live && v < nvec) {
+        VecIO<T, EPV>::load(pc + static_cast<int64_t>(v) * EPV, x[i]);
+        VecIO<T, EPV>::load(pz + static_cast<int64_t>(v) * EPV, z[i]);
+      }
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) {
+        const float d = x[i][c] - z[i][c];
+        D = fmaxf(D, fabsf(d));
+        C = fmaxf(C, fabsf(z[i][c]));
+        m[i][c] = delta ? d : x[i][c];
+      }
+    }
+    D = group_max(D, G);
+    C = group_max(C, G);
+    const float thr = eps * C;
+    const bool send = live && D > thr;
+    const bool head = live && lg == 0;
+    if (head) mask[row] = send ? 1 : 0;
+    sent_here += __popcll(__ballot(head && send));
+    encode_row<T, EPV, NIT, BITS, QS>(send, lg, G, nvec, x, z, m, commit, delta, codes_scratch + r * rb,
+                                      meta_scratch + 2 * r, pz);
+  }
+  __shared__ int wave_cnt[kQuantThreads / 64];
+  if (lane == 0) wave_cnt[wave] = sent_here;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int t = 0;
+    for (int w = 0; w < kQuantThreads / 64; ++w) t += wave_cnt[w];
+    block_counts[blockIdx.x] = t;
+  }
+}
+
+// codes[k] = scratch[idx[k]], meta[k] = meta_scratch[idx[k]] for k < *n_sent, rows of rb bytes moved
+// in units of U bytes by groups of 16 lanes.
+template <typename U>
+__global__ __launch_bounds__(256) void gather_codes_kernel(const uint8_t* __restrict__ scratch,
+                                                           const float* __restrict__ meta_scratch,
+                                                           const int* __restrict__ idx, const int* __restrict__ n_sent_p,
+                                                           int64_t rb, uint8_t* __restrict__ codes,
+                                                           float* __restrict__ meta) {
+  const int n_sent = *n_sent_p;
+  const int k = blockIdx.x * 16 + (threadIdx.x >> 4);
+  if (k >= n_sent) return;
+  const int l = threadIdx.x & 15;
+  const int64_t r = idx[k];
+  const U* src = reinterpret_cast<const U*>(scratch + r * rb);
+  U* dst = reinterpret_cast<U*>(codes + static_cast<int64_t>(k) * rb);
+  const int units = static_cast<int>(rb / sizeof(U));
+  for (int i = l; i < units; i += 16) dst[i] = src[i];
+  if (l < 2) meta[2 * static_cast<int64_t>(k) + l] = meta_scratch[2 * r + l];
 }
 
 template <typename T, int EPV, int NIT, int BITS, int QS>
@@ -246,6 +346,17 @@ static bool row_shape(int32_t dim, int epv, RowShape* s) {
   else if (bits == 8) { CDF_DISPATCH_EPV(K, T, 8, CDF_Q_SYMMETRIC, epv, nit, __VA_ARGS__) }        \
   else { CDF_DISPATCH_EPV(K, T, 4, CDF_Q_SYMMETRIC, epv, nit, __VA_ARGS__) }
 
+size_t filter_workspace_bytes(int64_t n_rows);
+int scan_and_compact(const uint8_t* mask, int n_rows, int* counts, int* offsets, int32_t* idx, int32_t* n_sent,
+                     hipStream_t st);
+
+// Workspace of the one-pass test + message build: block counts and offsets, then row-indexed codes
+// and meta. Sized for 8-bit codes of `dim` elements (the largest quantised row).
+size_t test_encode_workspace_bytes(int64_t n_rows, int32_t dim) {
+  const size_t rows = static_cast<size_t>(n_rows > 0 ? n_rows : 0);
+  return filter_workspace_bytes(n_rows) + align_up(rows * static_cast<size_t>(dim), 256) + align_up(rows * 8, 256);
+}
+
 }  // namespace cdf
 
 using namespace cdf;
@@ -332,3 +443,68 @@ extern "C" int cdf_dequantize(const uint8_t* codes, const float* meta, const int
   CDF_LAUNCH_CHECK("cdf_dequantize");
   return CDF_OK;
 }
+
+namespace cdf {
+
+// Cache test followed by the message build, as the layer steps need them. One pass over the rows
+// when the test is the L-infinity one, the messages are quantised and the workspace is large
+// enough (test_encode_workspace_bytes); otherwise cdf_cache_filter then cdf_quantize. Both routes
+// compute every row with the same instruction sequence: mask, idx, codes, meta and the committed
+// cache are bit-identical.
+int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, int64_t ld, cdf_dtype dt, float eps,
+                    cdf_norm norm, int bits, cdf_qscheme qs, cdf_commit commit, int delta, uint8_t* mask, int32_t* idx,
+                    int32_t* n_sent, uint8_t* codes, float* meta, void* ws, size_t ws_bytes, void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  RowShape s = {};
+  const size_t esz = elem_bytes(dt);
+  const bool types_ok = (dt == CDF_F32 || dt == CDF_BF16) && (qs == CDF_Q_MINMAX || qs == CDF_Q_SYMMETRIC) &&
+                        (bits == 8 || bits == 4) && norm == CDF_NORM_LINF && n_rows > 0 && dim > 0 && ld >= dim &&
+                        cur && cached && mask && idx && n_sent && codes && meta && eps >= 0.0f && eps <= 3.0e38f &&
+                        (commit == CDF_COMMIT_NONE || commit == CDF_COMMIT_CUR || commit == CDF_COMMIT_DEQ);
+  const bool one_pass = types_ok && ws && aligned(ws, 256) && ws_bytes >= test_encode_workspace_bytes(n_rows, dim) &&
+                        aligned(cur, esz) && aligned(cached, esz) && aligned(meta, 8) && aligned(codes, 16) &&
+                        row_shape(dim, pick_epv(dim, ld, esz, cur, cached), &s);
+  if (!one_pass) {
+    const int rc = cdf_cache_filter(cur, cached, n_rows, dim, ld, dt, eps, norm, mask, idx, n_sent, ws, ws_bytes, stream);
+    if (rc != CDF_OK) return rc;
+    return cdf_quantize(cur, cached, idx, n_sent, n_rows, dim, ld, dt, bits, qs, commit, delta, codes, meta, stream);
+  }
+  const int nblocks = static_cast<int>(ceil_div(n_rows, kTestRows));
+  char* w = static_cast<char*>(ws);
+  int* counts = reinterpret_cast<int*>(w);
+  int* offsets = counts + nblocks + 1;
+  uint8_t* cs = reinterpret_cast<uint8_t*>(w + filter_workspace_bytes(n_rows));
+  float* ms = reinterpret_cast<float*>(w + filter_workspace_bytes(n_rows) +
+                                       align_up(static_cast<size_t>(n_rows) * static_cast<size_t>(dim), 256));
+  const int64_t rb = (static_cast<int64_t>(dim) * bits + 7) / 8;
+#define ARGS_F32 <<<nblocks, kQuantThreads, 0, st>>>(static_cast<const float*>(cur), static_cast<float*>(cached), n_rows, \
+                 dim, ld, eps, s.glog, (int)commit, delta ? 1 : 0, mask, counts, cs, ms)
+#define ARGS_BF16 <<<nblocks, kQuantThreads, 0, st>>>(static_cast<const bf16_t*>(cur), static_cast<bf16_t*>(cached), n_rows, \
+                 dim, ld, eps, s.glog, (int)commit, delta ? 1 : 0, mask, counts, cs, ms)
+#define CDF_DISPATCH_QQ(K, T, ...)                                                                         \
+  if (qs == CDF_Q_MINMAX && bits == 8) { CDF_DISPATCH_EPV(K, T, 8, CDF_Q_MINMAX, s.epv, s.nit, __VA_ARGS__) } \
+  else if (qs == CDF_Q_MINMAX) { CDF_DISPATCH_EPV(K, T, 4, CDF_Q_MINMAX, s.epv, s.nit, __VA_ARGS__) }      \
+  else if (bits == 8) { CDF_DISPATCH_EPV(K, T, 8, CDF_Q_SYMMETRIC, s.epv, s.nit, __VA_ARGS__) }            \
+  else { CDF_DISPATCH_EPV(K, T, 4, CDF_Q_SYMMETRIC, s.epv, s.nit, __VA_ARGS__) }
+  prof_begin(K_TEST_ENCODE, st);
+  if (dt == CDF_F32) { CDF_DISPATCH_QQ(test_encode_kernel, float, ARGS_F32) }
+  else { CDF_DISPATCH_QQ(test_encode_kernel, bf16_t, ARGS_BF16) }
+  prof_end(K_TEST_ENCODE, st);
+#undef ARGS_F32
+#undef ARGS_BF16
+#undef CDF_DISPATCH_QQ
+  CDF_LAUNCH_CHECK("test_and_encode/encode");
+  const int rc = scan_and_compact(mask, n_rows, counts, offsets, idx, n_sent, st);
+  if (rc != CDF_OK) return rc;
+  {
+    ProfScope ps(K_GATHER_CODES, st);
+    const unsigned grid = static_cast<unsigned>(ceil_div(n_rows, 16));
+    if (rb % 16 == 0) gather_codes_kernel<uint4><<<grid, 256, 0, st>>>(cs, ms, idx, n_sent, rb, codes, meta);
+    else if (rb % 4 == 0) gather_codes_kernel<uint32_t><<<grid, 256, 0, st>>>(cs, ms, idx, n_sent, rb, codes, meta);
+    else gather_codes_kernel<uint8_t><<<grid, 256, 0, st>>>(cs, ms, idx, n_sent, rb, codes, meta);
+  }
+  CDF_LAUNCH_CHECK("test_and_encode/gather");
+  return CDF_OK;
+}
+
+}  // namespace cdf

@@ -538,3 +538,48 @@ def test_adam_and_accumulate(cdf, oracle):
     cdf.cdf_accumulate(da, b.to(DEV))
     torch.cuda.synchronize()
     np.testing.assert_array_equal(to_np(da), (a + b).numpy())
+
+
+@pytest.mark.parametrize("dtype,f_in,bits,qs", [("f32", 128, 8, "minmax"), ("f32", 100, 4, "minmax"),
+                                                 ("bf16", 64, 4, "symmetric"), ("f32", 7, 8, "symmetric"),
+                                                 ("bf16", 256, 8, "minmax"), ("f32", 1024, 8, "minmax")])
+@pytest.mark.parametrize("delta,commit", [(True, "cur"), (False, "deq")])
+def test_one_pass_message_build_equals_the_two_entry_points(dtype, f_in, bits, qs, delta, commit):
+    """With a workspace of cdf_workspace_bytes the layer step tests and codes the halo rows in one pass;
+    cdf_cache_filter followed by cdf_quantize is the two-pass route. Mask, row list, codes, meta and the
+    committed cache must be bit-identical between the two."""
+    from paper_2408_00232_amd import binding as B
+    from paper_2408_00232_amd.layer import DeviceCsr, LayerBuffers
+    w = configs.shrink(configs.TINY, 1500)
+    P = configs.build_partition(w)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    QS = {"minmax": B.Q_MINMAX, "symmetric": B.Q_SYMMETRIC}[qs]
+    CM = {"cur": B.COMMIT_CUR, "deq": B.COMMIT_DEQ}[commit]
+    A = DeviceCsr(P.n_loc, P.n_loc + P.n_halo, P.rowptr, P.colidx, P.vals)
+    L = LayerBuffers(A, None, P.n_loc, P.n_halo, f_in, 16, dtype=tdt, bits=bits, qs=QS, need_dx=False)
+    g = torch.Generator().manual_seed(7)
+    L.xfull.copy_(torch.randn(P.n_loc + P.n_halo, f_in, generator=g).to(tdt))
+    cache0 = torch.randn(P.n_halo, f_in, generator=g)
+    cache0[::17] = 0                                            # zero cached rows: sent on any difference
+    fresh = cache0 * (1 + 0.08 * torch.randn(P.n_halo, f_in, generator=g))   # roughly half the rows pass the test
+    fresh[::17] = torch.randn(fresh[::17].shape, generator=g)
+    fresh[5::23] = cache0[5::23]                                # unchanged rows: never sent
+    L.cache_sent.copy_(cache0.to(tdt))
+    L.halo_fresh.copy_(fresh.to(tdt))
+    L.W.copy_(torch.randn(f_in, 16, generator=g) * 0.1)
+    # two-pass route on copies
+    cache2 = L.cache_sent.clone()
+    mask2 = torch.zeros_like(L.mask); idx2 = torch.zeros_like(L.idx); n2 = torch.zeros_like(L.n_sent)
+    codes2 = torch.zeros_like(L.codes); meta2 = torch.zeros_like(L.meta)
+    ws = torch.zeros(L.workspace_bytes(), dtype=torch.uint8, device="cuda")
+    B.cdf_cache_filter(L.halo_fresh, cache2, 0.05, B.NORM_LINF, mask2, idx2, n2, ws)
+    B.cdf_quantize(L.halo_fresh, cache2, idx2, n2, P.n_halo, bits, QS, CM, delta, codes2, meta2)
+    B.cdf_gcn_layer_fwd(L.fwd_args(0.05, commit=CM, delta=delta), ws)
+    torch.cuda.synchronize()
+    n = int(L.n_sent.item())
+    assert 0 < n < P.n_halo and n == int(n2.item())
+    assert torch.equal(L.mask, mask2) and torch.equal(L.idx[:n], idx2[:n])
+    assert torch.equal(L.codes[:n * L.row_bytes], codes2[:n * L.row_bytes])
+    assert torch.equal(L.meta[:n].view(torch.int32), meta2[:n].view(torch.int32))
+    it = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(L.cache_sent.view(it), cache2.view(it))
