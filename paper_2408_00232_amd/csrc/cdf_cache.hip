@@ -148,6 +148,8 @@ __global__ __launch_bounds__(kFilterThreads) void filter_kernel(
 }
 
 // Exclusive scan of n counts by one block; offsets[i] = sum of counts[0..i), *total = sum.
+// Every thread takes kScanPer consecutive counts per pass, so a pass covers 1024 * kScanPer of them.
+constexpr int kScanPer = 8;
 __global__ __launch_bounds__(1024) void scan_kernel(const int* __restrict__ counts, int n,
                                                     int* __restrict__ offsets, int* __restrict__ total) {
   __shared__ int wsum[16];
@@ -155,10 +157,16 @@ __global__ __launch_bounds__(1024) void scan_kernel(const int* __restrict__ coun
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (threadIdx.x == 0) carry = 0;
   __syncthreads();
-  for (int base = 0; base < n; base += 1024) {
-    const int i = base + threadIdx.x;
-    const int v = i < n ? counts[i] : 0;
-    int incl = v;
+  for (int base = 0; base < n; base += 1024 * kScanPer) {
+    const int i0 = base + threadIdx.x * kScanPer;
+    int v[kScanPer];
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < kScanPer; ++j) {
+      v[j] = i0 + j < n ? counts[i0 + j] : 0;
+      mine += v[j];
+    }
+    int incl = mine;
     for (int off = 1; off < 64; off <<= 1) {
       const int t = __shfl_up(incl, off, kWave);
       if (lane >= off) incl += t;
@@ -168,7 +176,12 @@ __global__ __launch_bounds__(1024) void scan_kernel(const int* __restrict__ coun
     int wbase = 0;
     for (int w = 0; w < wave; ++w) wbase += wsum[w];
     const int c = carry;
-    if (i < n) offsets[i] = c + wbase + incl - v;
+    int run = c + wbase + incl - mine;
+#pragma unroll
+    for (int j = 0; j < kScanPer; ++j) {
+      if (i0 + j < n) offsets[i0 + j] = run;
+      run += v[j];
+    }
     __syncthreads();
     if (threadIdx.x == 1023) carry = c + wbase + incl;
     __syncthreads();
