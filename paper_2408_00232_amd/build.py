@@ -8,7 +8,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcdf.so")
 SOURCES = ["cdf_cache.hip", "cdf_quant.hip", "cdf_spmm.hip", "cdf_gemm.hip", "cdf_layer.hip", "cdf_train.hip",
-           "cdf_partition.hip"]
+           "cdf_partition.hip", "cdf_gemm_bf16.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wall", "-Wno-unused-function"]

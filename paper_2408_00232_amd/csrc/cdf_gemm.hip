@@ -331,12 +331,20 @@ static void launch_gemm(const GemmArgs& a, int Mdim, int Ndim, int slabs, int a_
 
 static bool vec4(const void* p, int64_t ld, size_t esz) { return aligned(p, 4 * esz) && ld % 4 == 0; }
 
+// bf16 matrix-core kernels for bf16-stored activations
+bool dense_fwd_bf16_ok(const void* M, int64_t ldm, int32_t f_in);
+int launch_dense_fwd_bf16(const void* M, int64_t ldm, const float* W, int32_t n, int32_t f_in, int32_t f_out, int relu,
+                          float* Z, float* H, void* ws, size_t ws_bytes, hipStream_t st);
+
 }  // namespace cdf
 
 using namespace cdf;
 
-extern "C" int cdf_dense_fwd(const void* M, int64_t ldm, cdf_dtype dt, const float* W, int32_t n, int32_t f_in,
-                             int32_t f_out, int relu, float* Z, float* H, void* stream) {
+namespace cdf {
+// The dense forward product with an optional workspace (the layer steps have one): with it the bf16
+// path splits the weight once per call instead of once per block.
+int dense_fwd_ws(const void* M, int64_t ldm, cdf_dtype dt, const float* W, int32_t n, int32_t f_in, int32_t f_out,
+                 int relu, float* Z, float* H, void* ws, size_t ws_bytes, void* stream) {
   hipStream_t st = static_cast<hipStream_t>(stream);
   CDF_REQUIRE(n >= 0 && f_in > 0 && f_out > 0 && ldm >= f_in, "cdf_dense_fwd: bad shape n=%d f_in=%d f_out=%d ldm=%lld",
               n, f_in, f_out, (long long)ldm);
@@ -349,9 +357,16 @@ extern "C" int cdf_dense_fwd(const void* M, int64_t ldm, cdf_dtype dt, const flo
   a.A = M; a.lda = ldm; a.B = W; a.out0 = Z; a.out1 = H; a.n = n; a.f = f_in; a.g = f_out; a.relu = relu ? 1 : 0;
   const int av = vec4(M, ldm, esz), bv = vec4(W, f_out, 4);
   if (dt == CDF_F32) launch_gemm<float, GEMM_FWD>(a, n, f_out, 1, av, bv, 0, st);
+  else if (dense_fwd_bf16_ok(M, ldm, f_in)) launch_dense_fwd_bf16(M, ldm, W, n, f_in, f_out, relu ? 1 : 0, Z, H, ws, ws_bytes, st);
   else launch_gemm<bf16_t, GEMM_FWD>(a, n, f_out, 1, av, bv, 0, st);
   CDF_LAUNCH_CHECK("cdf_dense_fwd");
   return CDF_OK;
+}
+}  // namespace cdf
+
+extern "C" int cdf_dense_fwd(const void* M, int64_t ldm, cdf_dtype dt, const float* W, int32_t n, int32_t f_in,
+                             int32_t f_out, int relu, float* Z, float* H, void* stream) {
+  return dense_fwd_ws(M, ldm, dt, W, n, f_in, f_out, relu, Z, H, nullptr, 0, stream);
 }
 
 extern "C" int cdf_dense_bwd(const void* M, int64_t ldm, cdf_dtype dt, const float* W, const float* Zs,

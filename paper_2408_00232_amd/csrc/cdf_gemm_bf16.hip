@@ -1,0 +1,225 @@
+// Dense transform for bf16-stored activations on the bf16 matrix cores (Sec. 3.1, Z = M W):
+// M [n x f] is bf16 and enters the MFMA unchanged; W [f x g] is fp32 and is split, while it is
+// staged into LDS, into a bf16 high part and a bf16 low part (w = hi + lo up to 2^-17 |w|), so
+// Z = M hi + M lo with fp32 accumulation inside v_mfma_f32_32x32x16_bf16 - two bf16 products at
+// sixteen times the fp32 matrix rate in place of one fp32 product.
+//
+// Tile: 128 x BN outputs (BN = 128 or 64) per block of four wavefronts (2 x 2), reduction in steps of 32.
+// LDS holds the operands k-contiguous per row (As[m][k], Bh[n][k], Bl[n][k]) so that a lane reads
+// its eight consecutive k values of a 32x32x16 operand with one 16-byte access. The next k-tile
+// is fetched into registers while the current one is multiplied.
+#include "cdf_common.h"
+
+namespace cdf {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kHM = 128;      // output rows per block
+constexpr int kHK = 32;       // reduction elements per LDS tile
+constexpr int kHS = kHK + 8;  // LDS row stride in bf16 elements (80 bytes: 16-byte aligned rows)
+constexpr int kHThreads = 256;
+
+// fp32 -> (hi, lo) bf16 bit patterns, both rounded to nearest even.
+__device__ __forceinline__ void split_bf16(float w, uint16_t& hi, uint16_t& lo) {
+  const __bf16 h = static_cast<__bf16>(w);
+  const __bf16 l = static_cast<__bf16>(w - static_cast<float>(h));
+  hi = __builtin_bit_cast(uint16_t, h);
+  lo = __builtin_bit_cast(uint16_t, l);
+}
+
+// W [f x g] fp32 -> Wh, Wl [g x f] bf16 (transposed: the reduction index becomes contiguous), done once
+// per product when the caller has workspace, so that the blocks of the product only copy.
+__global__ __launch_bounds__(256) void split_transpose_kernel(const float* __restrict__ W, int f, int g,
+                                                              uint16_t* __restrict__ Wh, uint16_t* __restrict__ Wl) {
+  __shared__ float tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;   // 32 x 8
+  const int k0 = blockIdx.x * 32, c0 = blockIdx.y * 32;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int k = k0 + ty + 8 * i, c = c0 + tx;
+    tile[ty + 8 * i][tx] = (k < f && c < g) ? W[static_cast<int64_t>(k) * g + c] : 0.0f;
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = c0 + ty + 8 * i, k = k0 + tx;
+    if (c < g && k < f) {
+      uint16_t hi, lo;
+      split_bf16(tile[tx][ty + 8 * i], hi, lo);
+      Wh[static_cast<int64_t>(c) * f + k] = hi;
+      Wl[static_cast<int64_t>(c) * f + k] = lo;
+    }
+  }
+}
+
+// PRE: Wh / Wl hold the split, transposed weight (see above) and W is unused; otherwise every block
+// splits its own part of W while staging it.
+template <int BN, bool PRE>
+__global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_t* __restrict__ M, int64_t ldm,
+                                                                     const float* __restrict__ W,
+                                                                     const uint16_t* __restrict__ Wh,
+                                                                     const uint16_t* __restrict__ Wl, int n, int f, int g,
+                                                                     int relu, float* __restrict__ Z,
+                                                                     float* __restrict__ H) {
+  constexpr int TM = 2, TN = BN / 64;
+  constexpr int BI = BN * (kHK / 8) / kHThreads;  // (column, k-block) items of the W tile per thread
+  __shared__ __attribute__((aligned(16))) uint16_t As[kHM][kHS];
+  __shared__ __attribute__((aligned(16))) uint16_t Bh[BN][kHS];
+  __shared__ __attribute__((aligned(16))) uint16_t Bl[BN][kHS];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.x * kHM, n0 = blockIdx.y * BN;
+
+  constexpr int AI = kHM * (kHK / 8) / kHThreads;   // 8-element chunks of the M tile per thread
+  u32x4 ra[AI];
+  float rb[PRE ? 1 : BI][8];    // BI items of 8 consecutive k for one output column (fp32, to be split)
+  u32x4 rh[PRE ? BI : 1], rl[PRE ? BI : 1];   // the same items, already split
+
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const int c = tid + kHThreads * i;
+      const int row = m0 + c / (kHK / 8), k = k0 + (c % (kHK / 8)) * 8;
+      if (row < n && k < f) ra[i] = *reinterpret_cast<const u32x4*>(M + static_cast<int64_t>(row) * ldm + k);
+      else ra[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < BI; ++i) {
+      const int item = tid + kHThreads * i;
+      const int col = n0 + item % BN, kb = k0 + (item / BN) * 8;
+      if (PRE) {
+        if (col < g && kb < f) {
+          rh[i] = *reinterpret_cast<const u32x4*>(Wh + static_cast<int64_t>(col) * f + kb);
+          rl[i] = *reinterpret_cast<const u32x4*>(Wl + static_cast<int64_t>(col) * f + kb);
+        } else {
+          rh[i] = rl[i] = u32x4{0u, 0u, 0u, 0u};
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          rb[i][j] = (col < g && kb + j < f) ? W[static_cast<int64_t>(kb + j) * g + col] : 0.0f;
+      }
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const int c = tid + kHThreads * i;
+      *reinterpret_cast<u32x4*>(&As[c / (kHK / 8)][(c % (kHK / 8)) * 8]) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < BI; ++i) {
+      const int item = tid + kHThreads * i;
+      if (PRE) {
+        *reinterpret_cast<u32x4*>(&Bh[item % BN][(item / BN) * 8]) = rh[i];
+        *reinterpret_cast<u32x4*>(&Bl[item % BN][(item / BN) * 8]) = rl[i];
+        continue;
+      }
+      uint16_t hi[8], lo[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) split_bf16(rb[i][j], hi[j], lo[j]);
+      u32x4 ph, pl;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        ph[q] = static_cast<uint32_t>(hi[2 * q]) | (static_cast<uint32_t>(hi[2 * q + 1]) << 16);
+        pl[q] = static_cast<uint32_t>(lo[2 * q]) | (static_cast<uint32_t>(lo[2 * q + 1]) << 16);
+      }
+      *reinterpret_cast<u32x4*>(&Bh[item % BN][(item / BN) * 8]) = ph;
+      *reinterpret_cast<u32x4*>(&Bl[item % BN][(item / BN) * 8]) = pl;
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  fetch(0);
+  for (int k0 = 0; k0 < f; k0 += kHK) {
+    stage();
+    __syncthreads();
+    if (k0 + kHK < f) fetch(k0 + kHK);
+#pragma unroll
+    for (int ks = 0; ks < kHK; ks += 16) {
+      // operand of a 32x32x16 product: lane (l32, lh) supplies row / column l32, k = lh*8 .. lh*8+7
+      bf16x8 a[TM], bh[TN], bl[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+        a[i] = *reinterpret_cast<const bf16x8*>(&As[wm * 64 + i * 32 + l32][ks + lh * 8]);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        bh[j] = *reinterpret_cast<const bf16x8*>(&Bh[wn * (BN / 2) + j * 32 + l32][ks + lh * 8]);
+        bl[j] = *reinterpret_cast<const bf16x8*>(&Bl[wn * (BN / 2) + j * 32 + l32][ks + lh * 8]);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bl[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bh[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+  }
+
+  // lane holds column l32 and rows (e/4)*8 + lh*4 + e%4 of each 32x32 tile
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * (BN / 2) + j * 32 + l32;
+      if (col >= g) continue;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+        if (row >= n) continue;
+        const float v = acc[i][j][e];
+        const int64_t off = static_cast<int64_t>(row) * g + col;
+        if (Z) Z[off] = v;
+        if (H) H[off] = relu ? (v > 0.0f ? v : 0.0f) : v;
+      }
+    }
+}
+
+// True when the bf16 matrix-core kernel can take the product (16-byte aligned rows of M).
+bool dense_fwd_bf16_ok(const void* M, int64_t ldm, int32_t f_in) {
+  return f_in % 8 == 0 && ldm % 8 == 0 && aligned(M, 16);
+}
+
+// Bytes of workspace with which the weight is split once instead of in every block.
+size_t dense_fwd_bf16_workspace_bytes(int32_t f_in, int32_t f_out) {
+  return align_up(static_cast<size_t>(f_in) * f_out * 2, 256) * 2;
+}
+
+int launch_dense_fwd_bf16(const void* M, int64_t ldm, const float* W, int32_t n, int32_t f_in, int32_t f_out, int relu,
+                          float* Z, float* H, void* ws, size_t ws_bytes, hipStream_t st) {
+  const bf16_t* m = static_cast<const bf16_t*>(M);
+  // 128 columns per block at most: the wider tile measured slower (three resident blocks per compute
+  // unit hide the barrier and LDS latency of this short pipeline better than one wide block)
+  const int bn = f_out > 64 ? 128 : 64;
+  const dim3 grid(static_cast<unsigned>(ceil_div(n, kHM)), static_cast<unsigned>(ceil_div(f_out, bn)));
+  const bool pre = ws && aligned(ws, 256) && ws_bytes >= dense_fwd_bf16_workspace_bytes(f_in, f_out);
+  uint16_t* wh = static_cast<uint16_t*>(ws);
+  uint16_t* wl = pre ? wh + align_up(static_cast<size_t>(f_in) * f_out * 2, 256) / 2 : nullptr;
+  ProfScope ps(K_GEMM_FWD, st);
+  if (pre) {
+    const dim3 sg(static_cast<unsigned>(ceil_div(f_in, 32)), static_cast<unsigned>(ceil_div(f_out, 32)));
+    split_transpose_kernel<<<sg, 256, 0, st>>>(W, f_in, f_out, wh, wl);
+  }
+#define CDF_BF16_FWD(BNV)                                                                                            \
+  if (pre) gemm_bf16_fwd_kernel<BNV, true><<<grid, kHThreads, 0, st>>>(m, ldm, W, wh, wl, n, f_in, f_out, relu, Z, H); \
+  else gemm_bf16_fwd_kernel<BNV, false><<<grid, kHThreads, 0, st>>>(m, ldm, W, nullptr, nullptr, n, f_in, f_out, relu, Z, H)
+  if (bn == 128) { CDF_BF16_FWD(128); }
+  else { CDF_BF16_FWD(64); }
+#undef CDF_BF16_FWD
+  return CDF_OK;
+}
+
+}  // namespace cdf

@@ -11,6 +11,8 @@ size_t filter_workspace_bytes(int64_t n_rows);
 size_t spmm_workspace_bytes(int64_t nnz, int32_t dim);
 size_t dense_workspace_bytes(int64_t n, int32_t f, int32_t g);
 size_t test_encode_workspace_bytes(int64_t n_rows, int32_t dim);
+int dense_fwd_ws(const void* M, int64_t ldm, cdf_dtype dt, const float* W, int32_t n, int32_t f_in, int32_t f_out,
+                 int relu, float* Z, float* H, void* ws, size_t ws_bytes, void* stream);
 int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, int64_t ld, cdf_dtype dt, float eps,
                     cdf_norm norm, int bits, cdf_qscheme qs, cdf_commit commit, int delta, uint8_t* mask, int32_t* idx,
                     int32_t* n_sent, uint8_t* codes, float* meta, void* ws, size_t ws_bytes, void* stream);
@@ -168,7 +170,7 @@ extern "C" int cdf_gcn_layer_fwd(const cdf_layer_fwd_args* p, void* ws, size_t w
   }
   rc = cdf_spmm_fwd(p->A, p->xfull, p->f_in, p->M, p->f_in, p->f_in, p->dt, w + fw, ws_bytes - fw, stream);
   if (rc != CDF_OK) return rc;
-  return cdf_dense_fwd(p->M, p->f_in, p->dt, p->W, p->n_loc, p->f_in, p->f_out, p->relu, p->Z, p->H, stream);
+  return dense_fwd_ws(p->M, p->f_in, p->dt, p->W, p->n_loc, p->f_in, p->f_out, p->relu, p->Z, p->H, w, ws_bytes, stream);
 }
 
 extern "C" int cdf_gcn_layer_bwd(const cdf_layer_bwd_args* p, void* ws, size_t ws_bytes, void* stream) {
