@@ -62,6 +62,8 @@ def _dt(a) -> int:
 
 
 def _rowmajor(a):
+    if a.ndim == 2 and a.size == 0:      # no rows (or no columns): any stride does
+        return max(a.shape[1], 1)
     assert a.ndim == 2 and a.strides[1] == a.itemsize and a.strides[0] % a.itemsize == 0
     return a.strides[0] // a.itemsize
 

@@ -109,3 +109,16 @@ def test_gather_rows_and_map_index():
     assert torch.equal(out[:500].cpu(), mp.cpu()[idx[:500].cpu().long()])
     assert (out[500:] == -1).all()
     B.cdf_gather_rows(view, idx[:0], dst)                  # empty list: nothing happens
+
+
+def test_single_partition_has_no_halo_and_still_trains(oracle):
+    """Degenerate case: one partition owns everything, there is nothing to exchange."""
+    from dataclasses import replace
+    w = replace(configs.shrink(configs.TINY, 500), parts=1)
+    tr, ref = _pair(w, oracle, eps0=0.05, adaptive=False)
+    assert tr.parts[0].n_halo == 0
+    for t in range(3):
+        st, rs = tr.epoch(), ref.epoch()
+        assert st.sent_fwd == st.sent_bwd == 0 and st.hit_rate == 1.0
+        assert abs(st.loss - rs["loss"]) <= 1e-5 * max(1.0, rs["loss"])
+        assert_rows_close(_logits_by_vertex(tr), rs["logits"], rel=2e-4, frob=2e-5, what=f"logits epoch {t}")

@@ -131,3 +131,15 @@ def test_mark_active_relu_kernels():
     h = torch.empty_like(z)
     B.cdf_relu_fwd(z, h)
     assert torch.equal(h.cpu(), torch.clamp_min(z.cpu(), 0))
+
+
+def test_single_device_has_no_mirrors(oracle):
+    """Degenerate case: one device holds every edge, every vertex is a master, no message travels."""
+    w = configs.shrink(configs.TINY, 500)
+    tr, ref = _pair(w, oracle, 1, eps0=0.05, adaptive=False)
+    assert tr.parts[0].n_mirror == 0
+    for t in range(3):
+        st, rs = tr.epoch(), ref.epoch()
+        assert st.gather == st.scatter == 0 and st.mirror_rows == 0
+        assert abs(st.loss - rs["loss"]) <= 1e-5 * max(1.0, rs["loss"])
+        assert_rows_close(tr.logits_by_vertex().numpy(), rs["logits"], rel=2e-4, frob=2e-5, what=f"logits epoch {t}")
