@@ -143,6 +143,8 @@ def main():
     ap.add_argument("--phi", type=float, default=0.01, help="fraction of local rows whose gradient changes")
     ap.add_argument("--order", default="auto", choices=["auto", "aggregate"],
                     help="auto: layers with f_out < f_in compute A (X W); aggregate: every layer computes (A X) W")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the same steps replayed from captured HIP graphs (reported beside the eager figures)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run the library's plain copy kernel on 1 GiB (for scaling hardware counters)")
@@ -191,6 +193,22 @@ def main():
 
     ms_per_step = elapsed / args.steps * 1e3
     ges = model.edges_per_step() / (elapsed / args.steps) / 1e9
+
+    graph_replay = None
+    if args.graph:
+        # launch-bound workloads (tiny, mid): the same steps as two captured graphs, one per input version
+        model.capture()
+        t_next = args.warmup + args.steps
+        for t in range(t_next, t_next + 2):
+            model.step(t)
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for t in range(t_next + 2, t_next + 2 + args.steps):
+            model.step(t)
+        torch.cuda.synchronize()
+        eg = time.perf_counter() - tg
+        graph_replay = {"ms_per_step": eg / args.steps * 1e3, "value": model.edges_per_step() / (eg / args.steps) / 1e9,
+                        "unit": "GE/s"}
 
     # per-kernel durations from the events recorded inside the timed region
     kernels = {}
@@ -316,6 +334,7 @@ def main():
         "kernels": kernels,
         "kernel_rooflines": per_kernel,
         "copy_ceiling_GBps": copy_gbs,
+        "graph_replay": graph_replay,
     }
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a sample ...")

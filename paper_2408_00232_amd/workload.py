@@ -78,9 +78,26 @@ class Model:
         nbytes = B.cdf_workspace_bytes(rows, max(max(d) for d in dims), max(P.nnz, 1))
         self.ws = torch.zeros(nbytes, dtype=torch.uint8, device=device)
 
+    def capture(self) -> None:
+        """Record the step for both input versions as HIP graphs; `step` replays them from then on.
+        The step allocates nothing and never synchronises, and the library clears its counters with
+        kernels (no memset nodes), so the capture holds kernel launches only. Run a few eager steps
+        first: capture records, it does not execute."""
+        self.graphs = []
+        for v in range(2):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                self._launch(v)
+            self.graphs.append(g)
+
     def step(self, t: int) -> None:
         """One pass of the hot path: all layers forward, then all layers backward."""
-        v = t & 1
+        if getattr(self, "graphs", None):
+            self.graphs[t & 1].replay()
+        else:
+            self._launch(t & 1)
+
+    def _launch(self, v: int) -> None:
         for li in range(len(self.layers)):
             (B.cdf_gcn_layer_tf_fwd if self.tf[li] else B.cdf_gcn_layer_fwd)(self.fwd[li][v], self.ws)
         for li in reversed(range(len(self.layers))):
