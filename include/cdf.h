@@ -89,7 +89,10 @@ int cdf_profile_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 /* Bytes of workspace that cover any call on matrices of at most max_rows rows (of a
  * feature matrix or of a CSR operand, whichever is larger), max_dim columns and
- * max_nnz stored entries. Host function, no device work. */
+ * max_nnz stored entries. Host function, no device work. The figure includes the
+ * row-indexed scratch (max_rows * (max_dim + 8) bytes) with which the layer steps test
+ * and code the halo rows in one pass; a layer step given less than that, but at least its
+ * own minimum, runs the two-pass route and produces the same bits. */
 size_t cdf_workspace_bytes(int64_t max_rows, int32_t max_dim, int64_t max_nnz);
 
 /* Bytes of one packed message row: dim*4 for CDF_Q_NONE, else ceil(dim*bits/8). The
@@ -167,6 +170,9 @@ int cdf_spmm_bwd(const cdf_csr* At, const void* dY, int64_t ldy, void* dX, int64
  * Dense transform (Sec. 3.1: Z = (A^ H) W, H' = sigma(Z), sigma = ReLU or identity) on
  * the matrix cores. M [n x f_in] type dt, W [f_in x f_out] fp32 row-major,
  * Z (nullable), H (nullable) [n x f_out] fp32 row-major, contiguous.
+ * fp32 M: fp32 matrix instructions. bf16 M with 16-byte aligned rows: bf16 matrix
+ * instructions with W split into a bf16 high and low part (W = hi + lo up to 2^-17 |W|),
+ * fp32 accumulation; other bf16 layouts widen M to fp32 on load.
  */
 int cdf_dense_fwd(const void* M, int64_t ldm, cdf_dtype dt, const float* W, int32_t n, int32_t f_in,
                   int32_t f_out, int relu, float* Z, float* H, void* stream);
