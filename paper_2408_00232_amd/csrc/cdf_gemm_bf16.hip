@@ -188,6 +188,157 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
     }
 }
 
+// ---- dM = dZ W^T for bf16-stored activations (Sec. 3.1, gradient w.r.t. the layer input) --------
+// dZ = dH * [Zs > 0] and W are both fp32 and both contiguous along the reduction index (the output
+// features), so each is split into bf16 high / low parts while it is staged:
+//   dM = dZh Wh^T + dZh Wl^T + dZl Wh^T          (the low x low term is below 2^-16 of the result)
+// The result is stored as bf16, which is the type the aggregation that follows reads.
+template <int BN>
+__global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float* __restrict__ dH,
+                                                                    const float* __restrict__ Zs,
+                                                                    const float* __restrict__ W, int n, int f, int g,
+                                                                    int relu, bf16_t* __restrict__ dM, int64_t ldo) {
+  constexpr int TM = 2, TN = BN / 64;
+  constexpr int AI = kHM * (kHK / 8) / kHThreads;
+  constexpr int BI = BN * (kHK / 8) / kHThreads;
+  __shared__ __attribute__((aligned(16))) uint16_t Ah[kHM][kHS];
+  __shared__ __attribute__((aligned(16))) uint16_t Al[kHM][kHS];
+  __shared__ __attribute__((aligned(16))) uint16_t Bh[BN][kHS];
+  __shared__ __attribute__((aligned(16))) uint16_t Bl[BN][kHS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.x * kHM, n0 = blockIdx.y * BN;
+
+  float ra[AI][8], rb[BI][8];
+  auto load8 = [](const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  };
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const int c = tid + kHThreads * i;
+      const int row = m0 + c / (kHK / 8), k = k0 + (c % (kHK / 8)) * 8;
+      if (row < n && k < g) {
+        load8(dH + static_cast<int64_t>(row) * g + k, ra[i]);
+        if (relu) {
+          float z[8];
+          load8(Zs + static_cast<int64_t>(row) * g + k, z);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) ra[i][j] = z[j] > 0.0f ? ra[i][j] : 0.0f;
+        }
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) ra[i][j] = 0.0f;
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < BI; ++i) {
+      const int item = tid + kHThreads * i;
+      const int col = n0 + item / (kHK / 8), k = k0 + (item % (kHK / 8)) * 8;
+      if (col < f && k < g) {
+        load8(W + static_cast<int64_t>(col) * g + k, rb[i]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) rb[i][j] = 0.0f;
+      }
+    }
+  };
+  auto put = [](const float (&v)[8], uint16_t* hi_dst, uint16_t* lo_dst) {
+    uint16_t hi[8], lo[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) split_bf16(v[j], hi[j], lo[j]);
+    u32x4 ph, pl;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      ph[q] = static_cast<uint32_t>(hi[2 * q]) | (static_cast<uint32_t>(hi[2 * q + 1]) << 16);
+      pl[q] = static_cast<uint32_t>(lo[2 * q]) | (static_cast<uint32_t>(lo[2 * q + 1]) << 16);
+    }
+    *reinterpret_cast<u32x4*>(hi_dst) = ph;
+    *reinterpret_cast<u32x4*>(lo_dst) = pl;
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const int c = tid + kHThreads * i;
+      put(ra[i], &Ah[c / (kHK / 8)][(c % (kHK / 8)) * 8], &Al[c / (kHK / 8)][(c % (kHK / 8)) * 8]);
+    }
+#pragma unroll
+    for (int i = 0; i < BI; ++i) {
+      const int item = tid + kHThreads * i;
+      put(rb[i], &Bh[item / (kHK / 8)][(item % (kHK / 8)) * 8], &Bl[item / (kHK / 8)][(item % (kHK / 8)) * 8]);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  fetch(0);
+  for (int k0 = 0; k0 < g; k0 += kHK) {
+    stage();
+    __syncthreads();
+    if (k0 + kHK < g) fetch(k0 + kHK);
+#pragma unroll
+    for (int ks = 0; ks < kHK; ks += 16) {
+      bf16x8 ah[TM], al[TM], bh[TN], bl[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        ah[i] = *reinterpret_cast<const bf16x8*>(&Ah[wm * 64 + i * 32 + l32][ks + lh * 8]);
+        al[i] = *reinterpret_cast<const bf16x8*>(&Al[wm * 64 + i * 32 + l32][ks + lh * 8]);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        bh[j] = *reinterpret_cast<const bf16x8*>(&Bh[wn * (BN / 2) + j * 32 + l32][ks + lh * 8]);
+        bl[j] = *reinterpret_cast<const bf16x8*>(&Bl[wn * (BN / 2) + j * 32 + l32][ks + lh * 8]);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[i], bh[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bl[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[i], bh[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * (BN / 2) + j * 32 + l32;
+      if (col >= f) continue;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+        if (row >= n) continue;
+        float one[1] = {acc[i][j][e]};
+        VecIO<bf16_t, 1>::store(dM + static_cast<int64_t>(row) * ldo + col, one);
+      }
+    }
+}
+
+bool dense_bwd_bf16_ok(const void* M, const float* W, const float* Zs, const float* dH, int32_t f_out) {
+  return f_out % 8 == 0 && aligned(W, 16) && aligned(dH, 16) && (!Zs || aligned(Zs, 16)) && aligned(M, 2);
+}
+
+int launch_dense_dm_bf16(const float* dH, const float* Zs, const float* W, int32_t n, int32_t f_in, int32_t f_out,
+                         int relu, void* dM, int64_t lddm, hipStream_t st) {
+  ProfScope ps(K_GEMM_DM, st);
+  const int bn = f_in > 64 ? 128 : 64;
+  const dim3 grid(static_cast<unsigned>(ceil_div(n, kHM)), static_cast<unsigned>(ceil_div(f_in, bn)));
+  bf16_t* o = static_cast<bf16_t*>(dM);
+  if (bn == 128) gemm_bf16_dm_kernel<128><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
+  else gemm_bf16_dm_kernel<64><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
+  return CDF_OK;
+}
+
 // True when the bf16 matrix-core kernel can take the product (16-byte aligned rows of M).
 bool dense_fwd_bf16_ok(const void* M, int64_t ldm, int32_t f_in) {
   return f_in % 8 == 0 && ldm % 8 == 0 && aligned(M, 16);
