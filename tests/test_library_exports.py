@@ -88,3 +88,43 @@ def test_eps_controller_host_function(lib):
     assert n >= 8
     p = B.cdf_eps_params(0.001, 0.02, 0.3, 0.001, 0.01, 1.05, 0.9, 1)
     assert abs(B.cdf_eps_update(0.05, 0.60, 0.50, p)[0] - 0.0525) < 2e-7
+
+
+def test_new_entry_points_validate_on_the_host(lib):
+    """Bad arguments are refused before anything is launched (so this runs without a GPU)."""
+    from paper_2408_00232_amd import binding as B
+    c32, c64, cf = ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+    assert lib.cdf_gather_rows(None, c64(4), None, c32(-1), c32(4), 0, None, c64(4), None) == B.ERR_INVALID_ARG
+    assert lib.cdf_gather_rows(None, c64(2), None, c32(3), c32(4), 0, None, c64(4), None) == B.ERR_INVALID_ARG  # ld < dim
+    assert lib.cdf_gather_rows(None, c64(4), None, c32(0), c32(4), 0, None, c64(4), None) == B.OK               # no rows
+    assert lib.cdf_map_index(None, None, c32(-1), None, None, None) == B.ERR_INVALID_ARG
+    assert lib.cdf_map_index(None, None, c32(0), None, None, None) == B.OK
+    assert lib.cdf_mark_rows(None, None, c32(5), None, c32(0), None, None) == B.ERR_INVALID_ARG
+    assert lib.cdf_relu_fwd(None, None, c64(-1), None) == B.ERR_INVALID_ARG
+    assert lib.cdf_relu_fwd(None, None, c64(0), None) == B.OK
+    assert lib.cdf_accumulate(None, None, c64(3), None) == B.ERR_INVALID_ARG
+    assert lib.cdf_adam_step(None, None, None, None, c64(4), cf(0.01), cf(0.9), cf(0.999), cf(1e-8), c32(0), None) == \
+        B.ERR_INVALID_ARG                                                                                      # t starts at 1
+    assert lib.cdf_adam_step(None, None, None, None, c64(4), cf(0.01), cf(1.0), cf(0.999), cf(1e-8), c32(1), None) == \
+        B.ERR_INVALID_ARG                                                                                      # beta1 = 1
+    assert lib.cdf_softmax_xent(None, None, c32(4), c32(0), cf(1.0), None, None, None, None, ctypes.c_size_t(0), None) == \
+        B.ERR_INVALID_ARG
+    assert lib.cdf_active_rows(None, None, c32(-2), None, None, None, None, ctypes.c_size_t(0), None) == B.ERR_INVALID_ARG
+    assert b"cdf_active_rows" in lib.cdf_last_error()
+
+
+def test_partition_structs_match_header_layout():
+    from paper_2408_00232_amd import binding as B
+    text = open(os.path.join(ROOT, "include", "cdf.h")).read()
+    for name, cls in (("cdf_ebv_params", B.cdf_ebv_params), ("cdf_cut_stats", B.cdf_cut_stats),
+                      ("cdf_eps_params", B.cdf_eps_params)):
+        end = re.search(r"\}\s*" + name + ";", text).start()
+        body = text[text.rindex("typedef struct {", 0, end) + len("typedef struct {"):end]
+        body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+        fields = []
+        for decl in body.split(";"):
+            for part in decl.strip().split(","):
+                names = re.findall(r"[A-Za-z_][A-Za-z0-9_]*", part)
+                if names:
+                    fields.append(names[-1])
+        assert fields == [f[0] for f in cls._fields_], name
