@@ -18,7 +18,6 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 constexpr int kBM = 128;
 constexpr int kBK = 32;
 constexpr int kGemmThreads = 256;
-constexpr int kSA = kBM + 4;
 
 enum GemmMode { GEMM_FWD = 0, GEMM_DM = 1, GEMM_DW = 2 };
 
@@ -64,7 +63,12 @@ __device__ __forceinline__ void load_quad_fast(const T* p, float (&v)[4]) { VecI
 
 template <typename T, int MODE, int BN, bool FAST>
 __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a_vec, int b_vec, int m_vec) {
-  constexpr int SB = BN + 4;
+  // LDS row strides. Tiles written with 16-byte vectors need rows that are multiples of 4 floats;
+  // tiles written transposed (one float per lane, k = 4 (tid % 8) + c, column = tid / 8 + 32 i) use a
+  // stride that is 2 mod 8, which spreads the 64 lanes of a store over all 32 banks (two lanes per
+  // bank, the minimum) instead of 16 banks.
+  constexpr int kSA = MODE == GEMM_DW ? kBM + 4 : kBM + 2;
+  constexpr int SB = MODE == GEMM_DM ? BN + 2 : BN + 4;
   constexpr int TN = BN / 64;   // 32-wide MFMA tiles per wavefront along n (waves are 2 x 2)
   constexpr int TM = 2;
   constexpr int BQ = BN / 32;   // B quads per thread
