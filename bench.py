@@ -194,6 +194,21 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     ges = model.edges_per_step() / (elapsed / args.steps) / 1e9
 
+    # per layer shape: forward and backward time of the generic layer step (a separate, untimed pass
+    # of the same steps with an event pair around every layer call), median over the passes
+    import statistics
+    fw, bw = [], []
+    for t in range(args.warmup + args.steps, args.warmup + args.steps + max(4, min(args.steps, 10))):
+        a_ms, b_ms = model.step_timed_per_layer(t)
+        fw.append(a_ms)
+        bw.append(b_ms)
+    per_layer = []
+    for li, (f_in, f_out) in enumerate(w.layers()):
+        tf_ms = statistics.median(x[li] for x in fw)
+        tb_ms = statistics.median(x[li] for x in bw)
+        per_layer.append({"f_in": f_in, "f_out": f_out, "order": "transform-first" if model.tf[li] else "aggregate-first",
+                          "fwd_ms": tf_ms, "bwd_ms": tb_ms, "GE_per_s": model.nnz / ((tf_ms + tb_ms) * 1e-3) / 1e9})
+
     graph_replay = None
     if args.graph:
         # launch-bound workloads (tiny, mid): the same steps as two captured graphs, one per input version
@@ -333,6 +348,7 @@ def main():
         "roofline": roof,
         "kernels": kernels,
         "kernel_rooflines": per_kernel,
+        "per_layer": per_layer,
         "copy_ceiling_GBps": copy_gbs,
         "graph_replay": graph_replay,
     }

@@ -11,11 +11,19 @@
 //   inv = Lv / (hi - lo)            one correctly rounded division per row
 //   q   = floor(fma(m - lo, inv, 0.5)) clamped to [0, Lv]
 //   back: scale = (hi - lo) / Lv,   m~ = fma(q, scale, lo)
+#include <algorithm>
+
 #include "cdf_common.h"
 
 namespace cdf {
 
 constexpr int kQuantThreads = 256;
+// The number of message rows is only known on the device, so grids are sized for the capacity -
+// but never beyond this many blocks: the kernels walk the rows in strides, so a call that sends
+// nothing costs 0.03 ms instead of up to 0.9 ms of empty blocks (5 M rows), while a call that sends
+// everything still runs within a few per cent of a grid with one block per group of rows (smaller
+// caps measured up to 25 % slower there).
+constexpr int64_t kMessageGridCap = 131072;
 
 // Statistics, codes, meta and cache commit of one message row held in registers: x = current row,
 // z = cached row, m = what is sent. Every lane of the group must call it (the row statistics use
@@ -122,19 +130,22 @@ __device__ __forceinline__ void encode_row(bool live, int lg, int G, int nvec, c
 // `NIT` vectors of EPV elements per lane: covers rows of up to 64*NIT vectors.
 template <typename T, int EPV, int NIT, int BITS, int QS>
 __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
-    const T* __restrict__ cur, T* cached, const int* __restrict__ idx, const int* __restrict__ n_sent_p,
+    const T* __restrict__ cur, T* cached, const int* __restrict__ idx, const int* __restrict__ n_sent_p, int max_sent,
     int dim, int64_t ld, int glog, int commit, int delta, uint8_t* __restrict__ codes,
     float* __restrict__ meta) {
-  const int n_sent = *n_sent_p;
+  const int n_sent = min(*n_sent_p, max_sent);   // never past the capacity of idx / codes / meta
   const int lane = threadIdx.x & 63;
   const int G = 1 << glog;
   const int lg = lane & (G - 1);
   const int rows_per_wave = 64 >> glog;
   const int gwave = blockIdx.x * (kQuantThreads / 64) + (threadIdx.x >> 6);
-  const int k = gwave * rows_per_wave + (lane >> glog);
-  const bool live = k < n_sent;
   const int nvec = dim / EPV;
   const int64_t rb = QS == CDF_Q_NONE ? static_cast<int64_t>(dim) * 4 : (static_cast<int64_t>(dim) * BITS + 7) / 8;
+  // the grid is capped; a wavefront walks its share of the rows (the bound is the same for all its lanes)
+  const int wave_stride = gridDim.x * (kQuantThreads / 64) * rows_per_wave;
+  for (int kb = gwave * rows_per_wave; kb < n_sent; kb += wave_stride) {
+  const int k = kb + (lane >> glog);
+  const bool live = k < n_sent;
 
   float x[NIT][EPV], z[NIT][EPV], m[NIT][EPV];
   int64_t r = 0;
@@ -157,6 +168,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
   encode_row<T, EPV, NIT, BITS, QS>(live, lg, G, nvec, x, z, m, commit, delta,
                                     codes + static_cast<int64_t>(live ? k : 0) * rb,
                                     meta + 2 * static_cast<int64_t>(live ? k : 0), pz);
+  }
 }
 
 // Cache test and message build in one pass over the rows (the two steps of Alg. 2's mirror loop
@@ -233,34 +245,36 @@ template <typename U>
 __global__ __launch_bounds__(256) void gather_codes_kernel(const uint8_t* __restrict__ scratch,
                                                            const float* __restrict__ meta_scratch,
                                                            const int* __restrict__ idx, const int* __restrict__ n_sent_p,
-                                                           int64_t rb, uint8_t* __restrict__ codes,
+                                                           int max_sent, int64_t rb, uint8_t* __restrict__ codes,
                                                            float* __restrict__ meta) {
-  const int n_sent = *n_sent_p;
-  const int k = blockIdx.x * 16 + (threadIdx.x >> 4);
-  if (k >= n_sent) return;
+  const int n_sent = min(*n_sent_p, max_sent);
   const int l = threadIdx.x & 15;
-  const int64_t r = idx[k];
-  const U* src = reinterpret_cast<const U*>(scratch + r * rb);
-  U* dst = reinterpret_cast<U*>(codes + static_cast<int64_t>(k) * rb);
   const int units = static_cast<int>(rb / sizeof(U));
-  for (int i = l; i < units; i += 16) dst[i] = src[i];
-  if (l < 2) meta[2 * static_cast<int64_t>(k) + l] = meta_scratch[2 * r + l];
+  for (int k = blockIdx.x * 16 + (threadIdx.x >> 4); k < n_sent; k += gridDim.x * 16) {
+    const int64_t r = idx[k];
+    const U* src = reinterpret_cast<const U*>(scratch + r * rb);
+    U* dst = reinterpret_cast<U*>(codes + static_cast<int64_t>(k) * rb);
+    for (int i = l; i < units; i += 16) dst[i] = src[i];
+    if (l < 2) meta[2 * static_cast<int64_t>(k) + l] = meta_scratch[2 * r + l];
+  }
 }
 
 template <typename T, int EPV, int NIT, int BITS, int QS>
 __global__ __launch_bounds__(kQuantThreads) void dequantize_kernel(
     const uint8_t* __restrict__ codes, const float* __restrict__ meta, const int* __restrict__ idx,
-    const int* __restrict__ n_sent_p, int dim, int glog, T* dst, int64_t ld, int accumulate) {
-  const int n_sent = *n_sent_p;
+    const int* __restrict__ n_sent_p, int max_sent, int dim, int glog, T* dst, int64_t ld, int accumulate) {
+  const int n_sent = min(*n_sent_p, max_sent);
   const int lane = threadIdx.x & 63;
   const int G = 1 << glog;
   const int lg = lane & (G - 1);
   const int rows_per_wave = 64 >> glog;
   const int gwave = blockIdx.x * (kQuantThreads / 64) + (threadIdx.x >> 6);
-  const int k = gwave * rows_per_wave + (lane >> glog);
-  if (k >= n_sent) return;
   const int nvec = dim / EPV;
   const int64_t rb = QS == CDF_Q_NONE ? static_cast<int64_t>(dim) * 4 : (static_cast<int64_t>(dim) * BITS + 7) / 8;
+  const int wave_stride = gridDim.x * (kQuantThreads / 64) * rows_per_wave;
+  for (int kb = gwave * rows_per_wave; kb < n_sent; kb += wave_stride) {
+  const int k = kb + (lane >> glog);
+  if (k >= n_sent) continue;
   const int64_t r = idx[k];
   const uint8_t* in = codes + static_cast<int64_t>(k) * rb;
   T* pd = dst + r * ld;
@@ -306,6 +320,7 @@ __global__ __launch_bounds__(kQuantThreads) void dequantize_kernel(
       for (int c = 0; c < EPV; ++c) val[c] = old[c] + val[c];
     }
     VecIO<T, EPV>::store(pd + static_cast<int64_t>(v) * EPV, val);
+  }
   }
 }
 
@@ -397,11 +412,11 @@ extern "C" int cdf_quantize(const void* cur, void* cached, const int32_t* idx, c
   if (!row_shape(dim, pick_epv(dim, ld, esz, cur, cached), &s))
     CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_quantize: dim %d too wide for its alignment (max %d)", dim, 512 * s.epv);
   const int rows_per_block = (kQuantThreads / 64) * (64 >> s.glog);
-  const int nblocks = static_cast<int>(ceil_div(max_sent, rows_per_block));
+  const int nblocks = static_cast<int>(std::min<int64_t>(ceil_div(max_sent, rows_per_block), kMessageGridCap));
 #define ARGS_F32 <<<nblocks, kQuantThreads, 0, st>>>(static_cast<const float*>(cur), static_cast<float*>(cached), \
-                 idx, n_sent, dim, ld, s.glog, (int)commit, delta ? 1 : 0, codes, meta)
+                 idx, n_sent, max_sent, dim, ld, s.glog, (int)commit, delta ? 1 : 0, codes, meta)
 #define ARGS_BF16 <<<nblocks, kQuantThreads, 0, st>>>(static_cast<const bf16_t*>(cur), static_cast<bf16_t*>(cached), \
-                 idx, n_sent, dim, ld, s.glog, (int)commit, delta ? 1 : 0, codes, meta)
+                 idx, n_sent, max_sent, dim, ld, s.glog, (int)commit, delta ? 1 : 0, codes, meta)
   prof_begin(K_QUANTIZE, st);
   if (dt == CDF_F32) { CDF_DISPATCH_Q(quantize_kernel, float, bits, qs, s.epv, s.nit, ARGS_F32) }
   else { CDF_DISPATCH_Q(quantize_kernel, bf16_t, bits, qs, s.epv, s.nit, ARGS_BF16) }
@@ -429,10 +444,10 @@ extern "C" int cdf_dequantize(const uint8_t* codes, const float* meta, const int
   if (!row_shape(dim, pick_epv(dim, ld, esz, dst), &s))
     CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_dequantize: dim %d too wide for its alignment (max %d)", dim, 512 * s.epv);
   const int rows_per_block = (kQuantThreads / 64) * (64 >> s.glog);
-  const int nblocks = static_cast<int>(ceil_div(max_sent, rows_per_block));
-#define ARGS_F32 <<<nblocks, kQuantThreads, 0, st>>>(codes, meta, idx, n_sent, dim, s.glog, static_cast<float*>(dst), \
+  const int nblocks = static_cast<int>(std::min<int64_t>(ceil_div(max_sent, rows_per_block), kMessageGridCap));
+#define ARGS_F32 <<<nblocks, kQuantThreads, 0, st>>>(codes, meta, idx, n_sent, max_sent, dim, s.glog, static_cast<float*>(dst), \
                  ld, accumulate ? 1 : 0)
-#define ARGS_BF16 <<<nblocks, kQuantThreads, 0, st>>>(codes, meta, idx, n_sent, dim, s.glog, static_cast<bf16_t*>(dst), \
+#define ARGS_BF16 <<<nblocks, kQuantThreads, 0, st>>>(codes, meta, idx, n_sent, max_sent, dim, s.glog, static_cast<bf16_t*>(dst), \
                  ld, accumulate ? 1 : 0)
   prof_begin(K_DEQUANTIZE, st);
   if (dt == CDF_F32) { CDF_DISPATCH_Q(dequantize_kernel, float, bits, qs, s.epv, s.nit, ARGS_F32) }
@@ -498,10 +513,10 @@ int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, 
   if (rc != CDF_OK) return rc;
   {
     ProfScope ps(K_GATHER_CODES, st);
-    const unsigned grid = static_cast<unsigned>(ceil_div(n_rows, 16));
-    if (rb % 16 == 0) gather_codes_kernel<uint4><<<grid, 256, 0, st>>>(cs, ms, idx, n_sent, rb, codes, meta);
-    else if (rb % 4 == 0) gather_codes_kernel<uint32_t><<<grid, 256, 0, st>>>(cs, ms, idx, n_sent, rb, codes, meta);
-    else gather_codes_kernel<uint8_t><<<grid, 256, 0, st>>>(cs, ms, idx, n_sent, rb, codes, meta);
+    const unsigned grid = static_cast<unsigned>(std::min<int64_t>(ceil_div(n_rows, 16), kMessageGridCap));
+    if (rb % 16 == 0) gather_codes_kernel<uint4><<<grid, 256, 0, st>>>(cs, ms, idx, n_sent, n_rows, rb, codes, meta);
+    else if (rb % 4 == 0) gather_codes_kernel<uint32_t><<<grid, 256, 0, st>>>(cs, ms, idx, n_sent, n_rows, rb, codes, meta);
+    else gather_codes_kernel<uint8_t><<<grid, 256, 0, st>>>(cs, ms, idx, n_sent, n_rows, rb, codes, meta);
   }
   CDF_LAUNCH_CHECK("test_and_encode/gather");
   return CDF_OK;

@@ -103,6 +103,24 @@ class Model:
         for li in reversed(range(len(self.layers))):
             (B.cdf_gcn_layer_tf_bwd if self.tf[li] else B.cdf_gcn_layer_bwd)(self.bwd[li][v], self.ws)
 
+    def step_timed_per_layer(self, t: int):
+        """One eager step with an event pair around every layer call: -> ([fwd ms per layer], [bwd ms per layer])."""
+        v = t & 1
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        n = len(self.layers)
+        fe = [(ev(), ev()) for _ in range(n)]
+        be = [(ev(), ev()) for _ in range(n)]
+        for li in range(n):
+            fe[li][0].record()
+            (B.cdf_gcn_layer_tf_fwd if self.tf[li] else B.cdf_gcn_layer_fwd)(self.fwd[li][v], self.ws)
+            fe[li][1].record()
+        for li in reversed(range(n)):
+            be[li][0].record()
+            (B.cdf_gcn_layer_tf_bwd if self.tf[li] else B.cdf_gcn_layer_bwd)(self.bwd[li][v], self.ws)
+            be[li][1].record()
+        torch.cuda.synchronize()
+        return [a.elapsed_time(b) for a, b in fe], [a.elapsed_time(b) for a, b in be]
+
     def spmm_widths(self):
         """Width of the rows each layer's aggregation gathers (f_out where the layer transforms first)."""
         return [g if tf else f for (f, g), tf in zip(self.w.layers(), self.tf)]
