@@ -75,9 +75,11 @@ class _PartLayer:
 class Trainer:
     def __init__(self, w: configs.Workload, device="cuda:0", eps0=None, lr=0.01, adaptive=True,
                  eps_params=None, qscheme=None, bits=None, norm=None, commit=B.COMMIT_CUR,
-                 train_fraction=0.6, signal=0.15, graph=None, keep_inputs=False):
+                 train_fraction=0.6, signal=0.15, graph=None, keep_inputs=False, gen_device="cpu"):
         """eps0: starting threshold (default: the workload's). adaptive=False keeps it fixed.
-        Messages are differences (Alg. 2) in both directions."""
+        Messages are differences (Alg. 2) in both directions. gen_device: where the seeded inputs
+        (graph, partitions, labels, features) are generated; the large workloads take minutes on
+        the host and seconds on the GPU (same graph and labels; normal draws agree to rounding)."""
         assert w.dtype == "f32", "the trainer steps fp32 workloads"
         self.w, self.device, self.lr, self.adaptive = w, device, lr, adaptive
         self.eps = float(w.eps if eps0 is None else eps0)
@@ -88,7 +90,8 @@ class Trainer:
         qs = _QS[w.qscheme if qscheme is None else qscheme]
         norm = _NORM[w.norm if norm is None else norm]
         self.bits, self.qs = bits, qs
-        g = graph if graph is not None else configs.build_graph(w, device="cpu")
+        g = graph if graph is not None else configs.build_graph(w, device=gen_device)
+        gd = g.lo.device
         masks = configs.owner_masks(w, g)
         parts = [graphs.extract_partition(g, m) for m in masks]
         self.parts = parts
@@ -101,9 +104,9 @@ class Trainer:
         # --- the task (inputs) ---
         y = labelgen.planted_labels(g, classes, w.seed)
         x0 = labelgen.planted_features(y, dims[0][0], w.seed, signal)
-        tm = labelgen.train_mask(g.n, w.seed, train_fraction)
+        tm = labelgen.train_mask(g.n, w.seed, train_fraction, device=gd)
         self.n_train = int(tm.sum().item())
-        self.inputs = dict(graph=g, x0=x0, labels=y, train=tm) if keep_inputs else None
+        self.inputs = dict(graph=g, x0=x0.cpu(), labels=y.cpu(), train=tm.cpu()) if keep_inputs else None
 
         # --- row numbering ---
         rows = [P.n_loc + P.n_halo for P in parts]
@@ -114,16 +117,16 @@ class Trainer:
             off.append(off[-1] + P.n_loc)
         self.base, self.off, self.rows_total = base, off, base[-1]
         assert self.rows_total < 2 ** 31 and off[-1] == g.n
-        tall_of = torch.empty(g.n, dtype=torch.int64)   # vertex -> its owner's row in the tall matrices
-        slot_of = torch.empty(g.n, dtype=torch.int64)   # vertex -> row in owner order
+        tall_of = torch.empty(g.n, dtype=torch.int64, device=gd)   # vertex -> its owner's row in the tall matrices
+        slot_of = torch.empty(g.n, dtype=torch.int64, device=gd)   # vertex -> row in owner order
         for j, P in enumerate(parts):
-            ar = torch.arange(P.n_loc, dtype=torch.int64)
+            ar = torch.arange(P.n_loc, dtype=torch.int64, device=gd)
             tall_of[P.owned] = base[j] + ar
             slot_of[P.owned] = off[j] + ar
         dev = device
         self.tall_map = [tall_of[P.halo].to(torch.int32).to(dev) for P in parts]
         self.slot_map = [slot_of[P.halo].to(torch.int32).to(dev) for P in parts]
-        self.vertex_of_slot = torch.cat([P.owned for P in parts])
+        self.vertex_of_slot = torch.cat([P.owned for P in parts]).cpu()
 
         # --- device state ---
         z = lambda *s, dt=torch.float32: torch.zeros(*s, dtype=dt, device=dev)
@@ -136,9 +139,10 @@ class Trainer:
         self.dlogits = z(g.n, classes)
         for j, P in enumerate(parts):
             self.X[0][base[j]:base[j] + P.n_loc] = x0[P.owned].to(dev)
-        lab = torch.where(tm, y, torch.full_like(y, -1))[self.vertex_of_slot]
+        vos = self.vertex_of_slot.to(gd)
+        lab = torch.where(tm, y, torch.full_like(y, -1))[vos]
         self.labels = lab.to(torch.int32).to(dev)
-        self.labels_all = y[self.vertex_of_slot].to(torch.int32).to(dev)
+        self.labels_all = y[vos].to(torch.int32).to(dev)
         self.W = [features.glorot(w.seed, 70 + l, f, gout).to(dev) for l, (f, gout) in enumerate(dims)]
         self.adam_m = [torch.zeros_like(W) for W in self.W]
         self.adam_v = [torch.zeros_like(W) for W in self.W]
