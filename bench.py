@@ -136,8 +136,8 @@ def cpu_baseline(model, budget_edges=12_000_000):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="share", help="tiny | mid | large | wide | share")
     ap.add_argument("--rho", type=float, default=0.37, help="fraction of halo rows refreshed per step")
     ap.add_argument("--phi", type=float, default=0.01, help="fraction of local rows whose gradient changes")
