@@ -36,6 +36,7 @@ def main(argv=None):
                     help="halo: owned rows + halo rows per partition; vertex-cut: master / mirror replicas (Sec. 3.2)")
     ap.add_argument("--devices-per-host", type=int, default=0, help="vertex-cut: hosts for the partitioner's gamma term")
     ap.add_argument("--gamma", type=float, default=0.1)
+    ap.add_argument("--streams", type=int, default=1, help="halo framing: streams the partitions of a phase are spread over")
     ap.add_argument("--gen-device", default="cpu", help="where the seeded inputs are generated (cpu or cuda:0)")
     ap.add_argument("--json", action="store_true", help="one JSON object per printed epoch")
     a = ap.parse_args(argv)
@@ -62,7 +63,7 @@ def main(argv=None):
               f"{sum(P.n_mirror for P in tr.parts)} mirrors, set-up {time.time() - t0:.1f} s", flush=True)
     else:
         tr = Trainer(w, eps0=a.eps0, lr=a.lr, adaptive=not a.fixed, eps_params=params, qscheme=a.qscheme, bits=a.bits,
-                     gen_device=a.gen_device)
+                     gen_device=a.gen_device, streams=a.streams)
         torch.cuda.synchronize()
         print(f"# {w.name}: {tr.n} vertices, {tr.p} partitions, layers {w.dims}, {tr.n_train} train rows, "
               f"{sum(P.n_halo for P in tr.parts)} halo rows, set-up {time.time() - t0:.1f} s", flush=True)

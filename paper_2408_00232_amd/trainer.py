@@ -75,7 +75,7 @@ class _PartLayer:
 class Trainer:
     def __init__(self, w: configs.Workload, device="cuda:0", eps0=None, lr=0.01, adaptive=True,
                  eps_params=None, qscheme=None, bits=None, norm=None, commit=B.COMMIT_CUR,
-                 train_fraction=0.6, signal=0.15, graph=None, keep_inputs=False, gen_device="cpu"):
+                 train_fraction=0.6, signal=0.15, graph=None, keep_inputs=False, gen_device="cpu", streams=1):
         """eps0: starting threshold (default: the workload's). adaptive=False keeps it fixed.
         Messages are differences (Alg. 2) in both directions. gen_device: where the seeded inputs
         (graph, partitions, labels, features) are generated; the large workloads take minutes on
@@ -156,6 +156,12 @@ class Trainer:
                      for P, r in zip(parts, rows))
         nbytes = max(nbytes, B.cdf_workspace_bytes(g.n, classes, 0))
         self.ws = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+        # streams > 1: the partitions' layer steps of one phase (they do not depend on each other) are
+        # spread over that many streams of default priority, each with a workspace of its own; small
+        # partitions do not fill the chip alone. Results do not depend on the number of streams.
+        self.n_streams = max(1, min(int(streams), p))
+        self.side = [torch.cuda.Stream(device=dev) for _ in range(self.n_streams)] if self.n_streams > 1 else []
+        self.side_ws = [torch.zeros(nbytes, dtype=torch.uint8, device=dev) for _ in self.side]
 
         # --- argument blocks ---
         es = 4
@@ -200,10 +206,36 @@ class Trainer:
             for j, P in enumerate(self.parts):
                 if P.n_halo:
                     B.cdf_gather_rows(self.X[l], self.tall_map[j], self.pl[j][l].halo_fresh)
+            self._per_partition(lambda j, ws, l=l: self._fwd_one(j, l, ws))
+
+    def _fwd_one(self, j, l, ws):
+        a = self.fwd_args[j][l]
+        a.eps = self.eps
+        B.cdf_gcn_layer_fwd(a, ws)
+
+    def _bwd_one(self, j, l, ws):
+        a = self.bwd_args[j][l]
+        a.eps = self.eps
+        B.cdf_gcn_layer_bwd(a, ws)
+
+    def _per_partition(self, fn) -> None:
+        """fn(j, workspace) for every partition: in turn on the current stream, or fanned out over the
+        side streams (fork after everything queued so far, join before anything queued afterwards)."""
+        if not self.side:
             for j in range(self.p):
-                a = self.fwd_args[j][l]
-                a.eps = self.eps
-                B.cdf_gcn_layer_fwd(a, self.ws)
+                fn(j, self.ws)
+            return
+        main = torch.cuda.current_stream()
+        fork = torch.cuda.Event()
+        fork.record(main)
+        for k, st in enumerate(self.side):
+            st.wait_event(fork)
+            with torch.cuda.stream(st):
+                for j in range(k, self.p, self.n_streams):
+                    fn(j, self.side_ws[k])
+            done = torch.cuda.Event()
+            done.record(st)
+            main.wait_event(done)
 
     def loss(self) -> None:
         B.cdf_softmax_xent(self.logits, self.labels, 1.0 / max(self.n_train, 1), self.dlogits, self.loss_sum,
@@ -211,10 +243,7 @@ class Trainer:
 
     def backward(self) -> None:
         for l in reversed(range(self.L)):
-            for j in range(self.p):
-                a = self.bwd_args[j][l]
-                a.eps = self.eps
-                B.cdf_gcn_layer_bwd(a, self.ws)
+            self._per_partition(lambda j, ws, l=l: self._bwd_one(j, l, ws))
             for j in range(1, self.p):                       # sum of the partitions' parameter gradients
                 B.cdf_accumulate(self.pl[0][l].dW, self.pl[j][l].dW)
             if l == 0:

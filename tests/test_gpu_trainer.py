@@ -122,3 +122,18 @@ def test_single_partition_has_no_halo_and_still_trains(oracle):
         assert st.sent_fwd == st.sent_bwd == 0 and st.hit_rate == 1.0
         assert abs(st.loss - rs["loss"]) <= 1e-5 * max(1.0, rs["loss"])
         assert_rows_close(_logits_by_vertex(tr), rs["logits"], rel=2e-4, frob=2e-5, what=f"logits epoch {t}")
+
+
+def test_streams_do_not_change_the_result(oracle):
+    """The partitions' layer steps of a phase spread over four streams: every buffer equals the
+    single-stream run bit for bit (the partitions do not touch each other's rows, sums keep their order)."""
+    from paper_2408_00232_amd.trainer import Trainer
+    w = configs.shrink(configs.TINY, 1500)
+    a = Trainer(w, eps0=0.05, adaptive=True, lr=0.02)
+    b = Trainer(w, eps0=0.05, adaptive=True, lr=0.02, streams=4)
+    for t in range(6):
+        sa, sb = a.epoch(), b.epoch()
+        assert (sa.sent_fwd, sa.sent_bwd, sa.eps, sa.loss) == (sb.sent_fwd, sb.sent_bwd, sb.eps, sb.loss)
+        assert torch.equal(a.logits, b.logits)
+        for l in range(a.L):
+            assert torch.equal(a.W[l], b.W[l])
