@@ -149,6 +149,19 @@ int cdf_dequantize(const uint8_t* codes, const float* meta, const int32_t* idx, 
                    cdf_dtype dt, int accumulate, void* stream);
 
 /*
+ * cdf_cache_filter followed by cdf_quantize on the same rows, in one pass over them where that is
+ * possible (L-infinity test, quantised messages, ws of cdf_workspace_bytes(n_rows, dim, 0) or more):
+ * a row is read once, tested, and - if it fails - coded and committed from the same registers; the
+ * messages are then moved into rank order. In every other case the two calls run one after the
+ * other. mask, idx, *n_sent, codes, meta and the committed cache are bit-identical to the two
+ * calls either way. Arguments as for those calls; capacity of idx / codes / meta = n_rows.
+ */
+int cdf_cache_filter_quantize(const void* cur, void* cached, int32_t n_rows, int32_t dim, int64_t ld,
+                              cdf_dtype dt, float eps, cdf_norm norm, int bits, cdf_qscheme qs,
+                              cdf_commit commit, int delta, uint8_t* mask, int32_t* idx, int32_t* n_sent,
+                              uint8_t* codes, float* meta, void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Aggregation over the normalised adjacency (Sec. 3.1, the product A^_i H of the forward
  * equation): Y[n_rows x dim] = A * X[n_cols x dim], fp32 accumulation in an order fixed by
  * the matrix shape alone (no atomics): bit-reproducible from run to run. `A` is a HOST pointer

@@ -523,3 +523,11 @@ int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, 
 }
 
 }  // namespace cdf
+
+extern "C" int cdf_cache_filter_quantize(const void* cur, void* cached, int32_t n_rows, int32_t dim, int64_t ld,
+                                         cdf_dtype dt, float eps, cdf_norm norm, int bits, cdf_qscheme qs,
+                                         cdf_commit commit, int delta, uint8_t* mask, int32_t* idx, int32_t* n_sent,
+                                         uint8_t* codes, float* meta, void* ws, size_t ws_bytes, void* stream) {
+  return cdf::test_and_encode(cur, cached, n_rows, dim, ld, dt, eps, norm, bits, qs, commit, delta, mask, idx, n_sent,
+                              codes, meta, ws, ws_bytes, stream);
+}

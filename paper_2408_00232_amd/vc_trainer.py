@@ -147,9 +147,8 @@ class VcTrainer:
             lo, hi = self.base[i] + P.n_master, self.base[i] + P.n
             ns = self._ns(ex, i, 0)
             idx, idxo = self.idx[:P.n_mirror], self.idx_owner[:P.n_mirror]
-            B.cdf_cache_filter(st.part[lo:hi], st.zc[lo:hi], eps, self.norm, self.mask, idx, ns, self.ws)
-            B.cdf_quantize(st.part[lo:hi], st.zc[lo:hi], idx, ns, P.n_mirror, self.bits, self.qs, B.COMMIT_CUR, True,
-                           self.codes, self.meta)
+            B.cdf_cache_filter_quantize(st.part[lo:hi], st.zc[lo:hi], eps, self.norm, self.bits, self.qs, B.COMMIT_CUR,
+                                        True, self.mask, idx, ns, self.codes, self.meta, self.ws)
             B.cdf_map_index(idx, ns, self.mmap[i], idxo)   # the master's row; the master adds and becomes active
             B.cdf_dequantize(self.codes, self.meta, idxo, ns, P.n_mirror, self.bits, self.qs, st.tot, True)
             B.cdf_mark_rows(idxo, ns, None, 0, self.active)
