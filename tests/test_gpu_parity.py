@@ -665,3 +665,58 @@ def test_cache_filter_quantize_equals_the_two_calls(dtype, dim, bits, qs, norm):
         assert 0 < outs[0][0] < R
         for a, b in zip(*outs):
             assert (a == b) if isinstance(a, int) else torch.equal(a, b)
+
+
+@pytest.mark.parametrize("bits,qs", [(8, 0), (4, 0), (8, 1)])
+def test_subnormal_and_extreme_rows_are_bit_exact(cdf, oracle, bits, qs):
+    """fp32 subnormals are not flushed and extreme ranges take the same path on both sides: rows
+    whose values, differences or min-max range are subnormal (so the reciprocal overflows), rows
+    near the largest finite value, constant rows and single-outlier rows - masks, codes, meta,
+    committed cache and recovered rows equal the oracle's bit for bit."""
+    R, F = 96, 64
+    g = torch.Generator().manual_seed(23)
+    base = torch.randn(R, F, generator=g)
+    scale = torch.ones(R, 1)
+    scale[0:16] = 1e-40                      # subnormal values
+    scale[16:32] = 3e-39                     # around the smallest normal
+    scale[32:48] = 1e38                      # near overflow (differences may overflow to inf)
+    scale[48:56] = 1e-30
+    cur = base * scale
+    cached = cur * (1 + 0.3 * torch.randn(R, F, generator=g))
+    cached[56:64] = 0                        # zero cache
+    cur[64:72] = 2.5e-41                     # constant subnormal rows (range 0)
+    cached[64:72] = 0
+    cur[72:80] = cached[72:80]               # unchanged rows
+    cur[80:88] = 0
+    cached[80:88] = 0
+    cur[80:88, 7] = 1e-44                    # a single subnormal outlier against a zero cache
+    cur, cached = cur.contiguous(), cached.contiguous()
+    ncur, ncached = cur.numpy().copy(), cached.numpy().copy()
+    dcur, dcached = cur.to(DEV), cached.to(DEV)
+    mask = torch.zeros(R, dtype=torch.uint8, device=DEV)
+    idx = torch.zeros(R, dtype=torch.int32, device=DEV)
+    n_sent = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ws = ws_for(cdf, R, F)
+    for norm in (0, 1):
+        cdf.cdf_cache_filter(dcur, dcached, 0.05, norm, mask, idx, n_sent, ws)
+        torch.cuda.synchronize()
+        omask, oidx = oracle.cache_filter(ncur, ncached, 0.05, norm)
+        np.testing.assert_array_equal(to_np(mask), omask)
+    cdf.cdf_cache_filter(dcur, dcached, 0.05, 0, mask, idx, n_sent, ws)
+    omask, oidx = oracle.cache_filter(ncur, ncached, 0.05, 0)
+    n = oidx.size
+    assert 40 < n < R
+    rb = cdf.cdf_code_row_bytes(F, bits, qs)
+    codes = torch.zeros(R * rb, dtype=torch.uint8, device=DEV)
+    meta = torch.zeros(R, 2, device=DEV)
+    cdf.cdf_quantize(dcur, dcached, idx, n_sent, R, bits, qs, 2, True, codes, meta)      # commit = recovered value
+    dst = torch.zeros(R, F, device=DEV)
+    cdf.cdf_dequantize(codes, meta, idx, n_sent, R, bits, qs, dst, accumulate=False)
+    torch.cuda.synchronize()
+    ocodes, ometa = oracle.quantize(ncur, ncached, oidx, bits, qs, 2, True)
+    np.testing.assert_array_equal(to_np(codes)[:n * rb].reshape(n, rb), ocodes)
+    np.testing.assert_array_equal(to_np(meta)[:n].view(np.uint32), ometa.view(np.uint32))
+    np.testing.assert_array_equal(to_np(dcached).view(np.uint32), ncached.view(np.uint32))
+    odst = np.zeros((R, F), np.float32)
+    oracle.dequantize(ocodes, ometa, oidx, odst, bits, qs, accumulate=False)
+    np.testing.assert_array_equal(to_np(dst).view(np.uint32), odst.view(np.uint32))
