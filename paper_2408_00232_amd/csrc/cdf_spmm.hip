@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
 // and in the memory-side cache; the CSR arrays are re-read once per slice (8 bytes per entry
 // against SW * 4 of features). Entries of a row are spread round-robin over the lane groups and
 // the groups' partial sums are combined when the row ends - a fixed order, no atomics.
-template <typename T, int EPV, int LPR>
+template <typename T, int EPV, int LPR, int U>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_sliced_kernel(
     const int64_t* __restrict__ rowptr, const int* __restrict__ colidx, const float* __restrict__ vals,
     int n_rows, int64_t nnz, const T* __restrict__ X, int64_t ldx, T* __restrict__ Y, T* __restrict__ Y2,
@@ -210,7 +210,6 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_sliced_kernel(
     float* __restrict__ ptail, int* __restrict__ tail_row, int kChunk) {
   constexpr int EPI = 64 / LPR;  // stored entries per gather instruction
   constexpr int SW = LPR * EPV;  // slice width in elements
-  constexpr int U = 4;           // gather instructions in flight
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + wave;
@@ -482,11 +481,14 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, i
   if (lpr > 0 && EPV * static_cast<int>(sizeof(T)) == 16) {
     const dim3 grid(nblocks, static_cast<unsigned>(dim / (lpr * EPV)));
     prof_begin(K_SPMM_SLICED, st);
-#define CDF_SLICED(LPRV)                                                                                        \
-  spmm_sliced_kernel<T, EPV, LPRV><<<grid, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, \
-                                                                  X, ldx, Y, Y2, ldy, dim, chunk_row, nc, phead, \
-                                                                  ptail, tail_row, chunk)
-    CDF_SLICED(8);
+#define CDF_SLICED(UV)                                                                                          \
+  spmm_sliced_kernel<T, EPV, 8, UV><<<grid, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, \
+                                                                   X, ldx, Y, Y2, ldy, dim, chunk_row, nc, phead, \
+                                                                   ptail, tail_row, chunk)
+    // gather instructions in flight per wavefront: long rows (the forward matrix of a power-law
+    // partition averages ~70 entries) run 2-3 % faster with eight, short rows (its transpose, ~20)
+    // with four - measured both ways
+    if (A->nnz >= static_cast<int64_t>(40) * A->n_rows) { CDF_SLICED(8); } else { CDF_SLICED(4); }
 #undef CDF_SLICED
     prof_end(K_SPMM_SLICED, st);
     CDF_LAUNCH_CHECK("cdf_spmm/sliced");
