@@ -307,11 +307,7 @@ extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_r
 #undef CDF_FILTER_CASE
   prof_end(K_FILTER, st);
   CDF_LAUNCH_CHECK("cdf_cache_filter/filter");
-  { ProfScope ps(K_SCAN, st); scan_kernel<<<1, 1024, 0, st>>>(counts, nblocks, offsets, n_sent); }
-  CDF_LAUNCH_CHECK("cdf_cache_filter/scan");
-  { ProfScope ps(K_COMPACT, st); compact_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(mask, n_rows, offsets, idx); }
-  CDF_LAUNCH_CHECK("cdf_cache_filter/compact");
-  return CDF_OK;
+  return scan_and_compact(mask, n_rows, counts, offsets, idx, n_sent, st);
 }
 
 extern "C" int cdf_active_rows(const uint8_t* flags, const int32_t* map, int32_t n_rows, uint8_t* mask, int32_t* idx,
@@ -333,9 +329,5 @@ extern "C" int cdf_active_rows(const uint8_t* flags, const int32_t* map, int32_t
   int* offsets = counts + nblocks + 1;
   flag_mask_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(flags, map, n_rows, mask, counts);
   CDF_LAUNCH_CHECK("cdf_active_rows/mask");
-  scan_kernel<<<1, 1024, 0, st>>>(counts, nblocks, offsets, n_sent);
-  CDF_LAUNCH_CHECK("cdf_active_rows/scan");
-  compact_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(mask, n_rows, offsets, idx);
-  CDF_LAUNCH_CHECK("cdf_active_rows/compact");
-  return CDF_OK;
+  return scan_and_compact(mask, n_rows, counts, offsets, idx, n_sent, st);
 }

@@ -492,22 +492,16 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, i
 #undef CDF_SLICED
     prof_end(K_SPMM_SLICED, st);
     CDF_LAUNCH_CHECK("cdf_spmm/sliced");
-    {
-      ProfScope ps(K_SPMM_FIXUP, st);
-      spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, Y2, ldy, dim,
-                                                                   A->n_rows);
-    }
-    CDF_LAUNCH_CHECK("cdf_spmm/fixup");
-    return CDF_OK;
+  } else {
+    prof_begin(K_SPMM, st);
+    if (np <= 1) spmm_kernel<T, EPV, 1> CDF_SPMM_ARGS;
+    else if (np <= 2) spmm_kernel<T, EPV, 2> CDF_SPMM_ARGS;
+    else if (np <= 4) spmm_kernel<T, EPV, 4> CDF_SPMM_ARGS;
+    else spmm_kernel<T, EPV, 8> CDF_SPMM_ARGS;
+    prof_end(K_SPMM, st);
+    CDF_LAUNCH_CHECK("cdf_spmm/main");
   }
-  prof_begin(K_SPMM, st);
-  if (np <= 1) spmm_kernel<T, EPV, 1> CDF_SPMM_ARGS;
-  else if (np <= 2) spmm_kernel<T, EPV, 2> CDF_SPMM_ARGS;
-  else if (np <= 4) spmm_kernel<T, EPV, 4> CDF_SPMM_ARGS;
-  else spmm_kernel<T, EPV, 8> CDF_SPMM_ARGS;
 #undef CDF_SPMM_ARGS
-  prof_end(K_SPMM, st);
-  CDF_LAUNCH_CHECK("cdf_spmm/main");
   {
     ProfScope ps(K_SPMM_FIXUP, st);
     spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, Y2, ldy, dim,
