@@ -149,42 +149,94 @@ __global__ __launch_bounds__(kFilterThreads) void filter_kernel(
 
 // Exclusive scan of n counts by one block; offsets[i] = sum of counts[0..i), *total = sum.
 // Every thread takes kScanPer consecutive counts per pass, so a pass covers 1024 * kScanPer of them.
+// Whole passes read and write 16-byte vectors without guards, and the counts of the next pass are
+// requested two passes ahead (straight-line code, so the wait before the sums leaves the later
+// requests in flight); the ragged last pass goes element by element.
 constexpr int kScanPer = 8;
+constexpr int kScanPass = 1024 * kScanPer;
+
+// One pass: v = this thread's counts; returns their exclusive start within the pass and adds the
+// pass total to carry. ws alternates between two buffers, so one barrier per pass is enough.
+__device__ __forceinline__ int scan_pass(const int (&v)[kScanPer], int (&ws)[16], int& carry) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int mine = 0;
+#pragma unroll
+  for (int j = 0; j < kScanPer; ++j) mine += v[j];
+  int incl = mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int t = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += t;
+  }
+  if (lane == 63) ws[wave] = incl;
+  __syncthreads();
+  int wbase = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < 16; ++w) {
+    const int t = ws[w];
+    if (w < wave) wbase += t;
+    all += t;
+  }
+  const int start = carry + wbase + incl - mine;
+  carry += all;
+  return start;
+}
+
 __global__ __launch_bounds__(1024) void scan_kernel(const int* __restrict__ counts, int n,
                                                     int* __restrict__ offsets, int* __restrict__ total) {
-  __shared__ int wsum[16];
-  __shared__ int carry;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (threadIdx.x == 0) carry = 0;
-  __syncthreads();
-  for (int base = 0; base < n; base += 1024 * kScanPer) {
+  __shared__ int wsum[2][16];
+  int carry = 0;  // sum of all earlier passes, the same in every thread
+  int pass = 0, base = 0;
+  const bool vec = ((reinterpret_cast<uintptr_t>(counts) | reinterpret_cast<uintptr_t>(offsets)) & 15) == 0;
+  if (vec && n >= kScanPass) {
+    const int4* src = reinterpret_cast<const int4*>(counts) + threadIdx.x * (kScanPer / 4);
+    int4* dst = reinterpret_cast<int4*>(offsets) + threadIdx.x * (kScanPer / 4);
+    // Three register sets take turns (this pass, the next, the one after); the loop is unrolled by
+    // three so that no set is ever copied - a copy would wait for its pending request.
+    int4 a0 = src[0], b0 = src[1], a1, b1, a2 = a0, b2 = b0;
+    {
+      const int q = 2 * kScanPass <= n ? kScanPass / 4 : 0;
+      a1 = src[q];
+      b1 = src[q + 1];
+    }
+    auto one_pass = [&](const int4& a, const int4& b, int4& fa, int4& fb) {
+      const int v[kScanPer] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+      // request the pass after next into the set that is free - always, so that every path has the
+      // same requests pending (past the last whole pass the first one is read again and not used)
+      const int q = base + 3 * kScanPass <= n ? (base + 2 * kScanPass) / 4 : 0;
+      fa = src[q];
+      fb = src[q + 1];
+      int run = scan_pass(v, wsum[pass & 1], carry);
+      int o[kScanPer];
+#pragma unroll
+      for (int j = 0; j < kScanPer; ++j) {
+        o[j] = run;
+        run += v[j];
+      }
+      dst[base / 4] = make_int4(o[0], o[1], o[2], o[3]);
+      dst[base / 4 + 1] = make_int4(o[4], o[5], o[6], o[7]);
+      base += kScanPass;
+      ++pass;
+    };
+    while (base + kScanPass <= n) {
+      one_pass(a0, b0, a2, b2);
+      if (base + kScanPass > n) break;
+      one_pass(a1, b1, a0, b0);
+      if (base + kScanPass > n) break;
+      one_pass(a2, b2, a1, b1);
+    }
+  }
+  for (; base < n; base += kScanPass, ++pass) {
     const int i0 = base + threadIdx.x * kScanPer;
     int v[kScanPer];
-    int mine = 0;
 #pragma unroll
-    for (int j = 0; j < kScanPer; ++j) {
-      v[j] = i0 + j < n ? counts[i0 + j] : 0;
-      mine += v[j];
-    }
-    int incl = mine;
-    for (int off = 1; off < 64; off <<= 1) {
-      const int t = __shfl_up(incl, off, kWave);
-      if (lane >= off) incl += t;
-    }
-    if (lane == 63) wsum[wave] = incl;
-    __syncthreads();
-    int wbase = 0;
-    for (int w = 0; w < wave; ++w) wbase += wsum[w];
-    const int c = carry;
-    int run = c + wbase + incl - mine;
+    for (int j = 0; j < kScanPer; ++j) v[j] = i0 + j < n ? counts[i0 + j] : 0;
+    int run = scan_pass(v, wsum[pass & 1], carry);
 #pragma unroll
     for (int j = 0; j < kScanPer; ++j) {
       if (i0 + j < n) offsets[i0 + j] = run;
       run += v[j];
     }
-    __syncthreads();
-    if (threadIdx.x == 1023) carry = c + wbase + incl;
-    __syncthreads();
   }
   if (threadIdx.x == 0) *total = carry;
 }
@@ -238,7 +290,7 @@ static void launch_filter(const void* cur, const void* cached, int n_rows, int d
 }
 
 // Exclusive scan of per-block counts (blocks of kRowsPerBlock rows) and ordered compaction of the
-// mask into idx / *n_sent; counts and offsets each hold ceil(n_rows / kRowsPerBlock) + 1 ints.
+// mask into idx / *n_sent; counts holds ceil(n_rows / kRowsPerBlock) ints, offsets = counts + scan_stride.
 int scan_and_compact(const uint8_t* mask, int n_rows, int* counts, int* offsets, int32_t* idx, int32_t* n_sent,
                      hipStream_t st) {
   const int nblocks = static_cast<int>(ceil_div(n_rows, kRowsPerBlock));
@@ -253,7 +305,8 @@ int scan_and_compact(const uint8_t* mask, int n_rows, int* counts, int* offsets,
 }
 
 size_t filter_workspace_bytes(int64_t n_rows) {
-  return align_up(static_cast<size_t>(2 * (ceil_div(n_rows, kRowsPerBlock) + 1)) * sizeof(int), 256);
+  const int64_t nb = ceil_div(n_rows > 0 ? n_rows : 0, kRowsPerBlock);
+  return align_up(static_cast<size_t>(scan_stride(nb) + nb + 1) * sizeof(int), 256);
 }
 
 }  // namespace cdf
@@ -287,7 +340,7 @@ extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_r
     CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_cache_filter: workspace too small (%zu < %zu)", ws_bytes,
              filter_workspace_bytes(n_rows));
   int* counts = static_cast<int*>(ws);
-  int* offsets = counts + nblocks + 1;
+  int* offsets = counts + scan_stride(nblocks);
 
   const int epv = pick_epv(dim, ld, esz, cur, cached);
   const int nvec = dim / epv;
@@ -326,7 +379,7 @@ extern "C" int cdf_active_rows(const uint8_t* flags, const int32_t* map, int32_t
     CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_active_rows: workspace too small (%zu < %zu)", ws_bytes,
              filter_workspace_bytes(n_rows));
   int* counts = static_cast<int*>(ws);
-  int* offsets = counts + nblocks + 1;
+  int* offsets = counts + scan_stride(nblocks);
   flag_mask_kernel<<<nblocks, kRowsPerBlock, 0, st>>>(flags, map, n_rows, mask, counts);
   CDF_LAUNCH_CHECK("cdf_active_rows/mask");
   return scan_and_compact(mask, n_rows, counts, offsets, idx, n_sent, st);

@@ -55,6 +55,10 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline size_t elem_bytes(cdf_dtype dt) { return dt == CDF_BF16 ? 2 : 4; }
 
+// Per-block counts and their exclusive offsets share one workspace area: counts first, offsets
+// `scan_stride` ints later (a multiple of 4, so that both start on the same 16-byte phase).
+inline int64_t scan_stride(int64_t nblocks) { return (nblocks + 1 + 3) / 4 * 4; }
+
 // Elements per lane-vector for rows of `dim` elements spaced `ld` apart starting at p0 / p1:
 // 4, 2 or 1, the widest for which every row start and every vector is naturally aligned.
 inline int pick_epv(int32_t dim, int64_t ld, size_t esz, const void* p0, const void* p1 = nullptr,

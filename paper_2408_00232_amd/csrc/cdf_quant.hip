@@ -487,7 +487,7 @@ int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, 
   const int nblocks = static_cast<int>(ceil_div(n_rows, kTestRows));
   char* w = static_cast<char*>(ws);
   int* counts = reinterpret_cast<int*>(w);
-  int* offsets = counts + nblocks + 1;
+  int* offsets = counts + scan_stride(nblocks);
   uint8_t* cs = reinterpret_cast<uint8_t*>(w + filter_workspace_bytes(n_rows));
   float* ms = reinterpret_cast<float*>(w + filter_workspace_bytes(n_rows) +
                                        align_up(static_cast<size_t>(n_rows) * static_cast<size_t>(dim), 256));
