@@ -87,6 +87,41 @@ def test_cache_filter(cdf, oracle, R, F, ld, dtype, norm):
     assert 0 < oidx.size < R or R < 10
 
 
+@pytest.mark.parametrize("R", [64 * 8192, 64 * 8192 * 3, 64 * 8192 * 2 + 64 * 5 + 17, 64 * 8192 - 1, 64 * 8192 * 4 + 1])
+def test_cache_filter_many_rows(cdf, oracle, R):
+    """Row counts whose per-block counts fill one or several whole passes of the scan (8192 counts
+    each, read as vectors), exactly or with a ragged rest, through the two-launch route and the
+    one-pass route; narrow rows keep the oracle quick."""
+    F = 4
+    cur, cached = make_pair(R, F, F, torch.float32, seed=R % 1000 + 5, frac_same=0.5)
+    dcur, dcached = cur.to(DEV), cached.to(DEV)
+    mask = torch.full((R,), 7, dtype=torch.uint8, device=DEV)
+    idx = torch.full((R,), -1, dtype=torch.int32, device=DEV)
+    n_sent = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    ws = ws_for(cdf, R, F)
+    omask, oidx = oracle.cache_filter(to_np(cur), to_np(cached), 0.05, 0)
+    assert 0 < oidx.size < R
+    cdf.cdf_cache_filter(dcur, dcached, 0.05, 0, mask, idx, n_sent, ws)
+    torch.cuda.synchronize()
+    assert int(n_sent.item()) == oidx.size
+    np.testing.assert_array_equal(to_np(mask), omask)
+    np.testing.assert_array_equal(to_np(idx)[:oidx.size], oidx)
+    # one-pass route (same scan, counts written by the fused kernel)
+    rb = cdf.cdf_code_row_bytes(F, 8, cdf.Q_MINMAX)
+    codes = torch.zeros(R * rb, dtype=torch.uint8, device=DEV)
+    meta = torch.zeros(R, 2, device=DEV)
+    mask.fill_(7); idx.fill_(-1); n_sent.fill_(-1)
+    cdf.cdf_cache_filter_quantize(dcur, dcached.clone(), 0.05, 0, 8, cdf.Q_MINMAX, cdf.COMMIT_CUR, True, mask, idx, n_sent,
+                                  codes, meta, ws)
+    torch.cuda.synchronize()
+    assert int(n_sent.item()) == oidx.size
+    np.testing.assert_array_equal(to_np(mask), omask)
+    np.testing.assert_array_equal(to_np(idx)[:oidx.size], oidx)
+    ocodes, ometa = oracle.quantize(to_np(cur), to_np(cached).copy(), oidx, 8, 0, 1, True)
+    np.testing.assert_array_equal(to_np(codes)[:oidx.size * rb].reshape(-1, rb), ocodes.reshape(-1, rb))
+    np.testing.assert_array_equal(to_np(meta)[:oidx.size], ometa)
+
+
 def test_cache_filter_edges(cdf, oracle):
     ws = ws_for(cdf, 1024, 64)
     n_sent = torch.full((1,), -1, dtype=torch.int32, device=DEV)
