@@ -150,7 +150,7 @@ int cdf_dequantize(const uint8_t* codes, const float* meta, const int32_t* idx, 
 
 /*
  * cdf_cache_filter followed by cdf_quantize on the same rows, in one pass over them where that is
- * possible (L-infinity test, quantised messages, ws of cdf_workspace_bytes(n_rows, dim, 0) or more):
+ * possible (quantised messages, ws of cdf_workspace_bytes(n_rows, dim, 0) or more):
  * a row is read once, tested, and - if it fails - coded and committed from the same registers; the
  * messages are then moved into rank order. In every other case the two calls run one after the
  * other. mask, idx, *n_sent, codes, meta and the committed cache are bit-identical to the two

@@ -172,7 +172,7 @@ __global__ __launch_bounds__(kQuantThreads) void quantize_kernel(
 }
 
 // Cache test and message build in one pass over the rows (the two steps of Alg. 2's mirror loop
-// back to back): every row is read once, tested (L-infinity form), and - if it fails the test -
+// back to back): every row is read once, tested (either norm), and - if it fails the test -
 // coded and committed from the same registers. The position of a row's message in the output is
 // only known after the count of sent rows before it, so codes and meta go to a row-indexed
 // scratch area first and gather_codes_kernel moves them to their final place (one byte per
@@ -182,9 +182,10 @@ constexpr int kTestRows = kRowsPerBlock;
 
 template <typename T, int EPV, int NIT, int BITS, int QS>
 __global__ __launch_bounds__(kQuantThreads) void test_encode_kernel(
-    const T* __restrict__ cur, T* cached, int n_rows, int dim, int64_t ld, float eps, int glog, int commit, int delta,
-    uint8_t* __restrict__ mask, int* __restrict__ block_counts, uint8_t* __restrict__ codes_scratch,
+    const T* __restrict__ cur, T* cached, int n_rows, int dim, int64_t ld, float eps, int norm, int glog, int commit,
+    int delta, uint8_t* __restrict__ mask, int* __restrict__ block_counts, uint8_t* __restrict__ codes_scratch,
     float* __restrict__ meta_scratch) {
+  constexpr int NACC = 4 / EPV;  // L2 norm: accumulators per lane-component, as in the cache test
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int G = 1 << glog;
   const int lg = lane & (G - 1), sub = lane >> glog;
@@ -201,7 +202,6 @@ __global__ __launch_bounds__(kQuantThreads) void test_encode_kernel(
     const T* pc = cur + r * ld;
     T* pz = cached + r * ld;
     float x[NIT][EPV], z[NIT][EPV], m[NIT][EPV];
-    float D = 0.0f, C = 0.0f;
 #pragma unroll
     for (int i = 0; i < NIT; ++i) {
       const int v = lg + i * G;
@@ -212,16 +212,68 @@ __global__ __launch_bounds__(kQuantThreads) void test_encode_kernel(
         VecIO<T, EPV>::load(pz + static_cast<int64_t>(v) * EPV, z[i]);
       }
 #pragma unroll
-      for (int c = 0; c < EPV; ++c) {
-        const float d = x[i][c] - z[i][c];
-        D = fmaxf(D, fabsf(d));
-        C = fmaxf(C, fabsf(z[i][c]));
-        m[i][c] = delta ? d : x[i][c];
-      }
+      for (int c = 0; c < EPV; ++c) m[i][c] = delta ? x[i][c] - z[i][c] : x[i][c];
     }
-    D = group_max(D, G);
-    C = group_max(C, G);
-    const float thr = eps * C;
+    // the test, in the cache test's own order of operations (masks must agree bit for bit)
+    float D, C, thr;
+    if (norm == CDF_NORM_LINF) {
+      D = 0.0f;
+      C = 0.0f;
+#pragma unroll
+      for (int i = 0; i < NIT; ++i)
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) {
+          D = fmaxf(D, fabsf(x[i][c] - z[i][c]));
+          C = fmaxf(C, fabsf(z[i][c]));
+        }
+      D = group_max(D, G);
+      C = group_max(C, G);
+      thr = eps * C;
+    } else {
+      // vector i of a lane feeds accumulator i mod NACC; lanes past the row end add exact zeros
+      float ad[NACC][EPV], ac[NACC][EPV];
+#pragma unroll
+      for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) ad[a][c] = ac[a][c] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < NIT; ++i)
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) {
+          const float d = x[i][c] - z[i][c];
+          ad[i % NACC][c] = __fmaf_rn(d, d, ad[i % NACC][c]);
+          ac[i % NACC][c] = __fmaf_rn(z[i][c], z[i][c], ac[i % NACC][c]);
+        }
+      float Da[NACC], Ca[NACC];
+#pragma unroll
+      for (int a = 0; a < NACC; ++a) {
+        float d, c;
+        if (EPV == 4) {
+          d = (ad[a][0] + ad[a][1 % EPV]) + (ad[a][2 % EPV] + ad[a][3 % EPV]);
+          c = (ac[a][0] + ac[a][1 % EPV]) + (ac[a][2 % EPV] + ac[a][3 % EPV]);
+        } else if (EPV == 2) {
+          d = ad[a][0] + ad[a][1 % EPV];
+          c = ac[a][0] + ac[a][1 % EPV];
+        } else {
+          d = ad[a][0];
+          c = ac[a][0];
+        }
+        Da[a] = group_sum(d, G);
+        Ca[a] = group_sum(c, G);
+      }
+      if (NACC == 4) {
+        D = (Da[0] + Da[1 % NACC]) + (Da[2 % NACC] + Da[3 % NACC]);
+        C = (Ca[0] + Ca[1 % NACC]) + (Ca[2 % NACC] + Ca[3 % NACC]);
+      } else if (NACC == 2) {
+        D = Da[0] + Da[1 % NACC];
+        C = Ca[0] + Ca[1 % NACC];
+      } else {
+        D = Da[0];
+        C = Ca[0];
+      }
+      const float e2 = eps * eps;
+      thr = e2 * C;
+    }
     const bool send = live && D > thr;
     const bool head = live && lg == 0;
     if (head) mask[row] = send ? 1 : 0;
@@ -462,7 +514,7 @@ extern "C" int cdf_dequantize(const uint8_t* codes, const float* meta, const int
 namespace cdf {
 
 // Cache test followed by the message build, as the layer steps need them. One pass over the rows
-// when the test is the L-infinity one, the messages are quantised and the workspace is large
+// when the messages are quantised and the workspace is large
 // enough (test_encode_workspace_bytes); otherwise cdf_cache_filter then cdf_quantize. Both routes
 // compute every row with the same instruction sequence: mask, idx, codes, meta and the committed
 // cache are bit-identical.
@@ -473,7 +525,7 @@ int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, 
   RowShape s = {};
   const size_t esz = elem_bytes(dt);
   const bool types_ok = (dt == CDF_F32 || dt == CDF_BF16) && (qs == CDF_Q_MINMAX || qs == CDF_Q_SYMMETRIC) &&
-                        (bits == 8 || bits == 4) && norm == CDF_NORM_LINF && n_rows > 0 && dim > 0 && ld >= dim &&
+                        (bits == 8 || bits == 4) && (norm == CDF_NORM_LINF || norm == CDF_NORM_L2) && n_rows > 0 && dim > 0 && ld >= dim &&
                         cur && cached && mask && idx && n_sent && codes && meta && eps >= 0.0f && eps <= 3.0e38f &&
                         (commit == CDF_COMMIT_NONE || commit == CDF_COMMIT_CUR || commit == CDF_COMMIT_DEQ);
   const bool one_pass = types_ok && ws && aligned(ws, 256) && ws_bytes >= test_encode_workspace_bytes(n_rows, dim) &&
@@ -493,9 +545,9 @@ int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, 
                                        align_up(static_cast<size_t>(n_rows) * static_cast<size_t>(dim), 256));
   const int64_t rb = (static_cast<int64_t>(dim) * bits + 7) / 8;
 #define ARGS_F32 <<<nblocks, kQuantThreads, 0, st>>>(static_cast<const float*>(cur), static_cast<float*>(cached), n_rows, \
-                 dim, ld, eps, s.glog, (int)commit, delta ? 1 : 0, mask, counts, cs, ms)
+                 dim, ld, eps, (int)norm, s.glog, (int)commit, delta ? 1 : 0, mask, counts, cs, ms)
 #define ARGS_BF16 <<<nblocks, kQuantThreads, 0, st>>>(static_cast<const bf16_t*>(cur), static_cast<bf16_t*>(cached), n_rows, \
-                 dim, ld, eps, s.glog, (int)commit, delta ? 1 : 0, mask, counts, cs, ms)
+                 dim, ld, eps, (int)norm, s.glog, (int)commit, delta ? 1 : 0, mask, counts, cs, ms)
 #define CDF_DISPATCH_QQ(K, T, ...)                                                                         \
   if (qs == CDF_Q_MINMAX && bits == 8) { CDF_DISPATCH_EPV(K, T, 8, CDF_Q_MINMAX, s.epv, s.nit, __VA_ARGS__) } \
   else if (qs == CDF_Q_MINMAX) { CDF_DISPATCH_EPV(K, T, 4, CDF_Q_MINMAX, s.epv, s.nit, __VA_ARGS__) }      \
