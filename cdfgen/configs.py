@@ -2,10 +2,8 @@
 recipe into one partition's CSR blocks. `shrink` scales a recipe down (fewer
 vertices and samples) for tests that must finish on the host in seconds.
 """
-from dataclasses import dataclass, field, replace
+from dataclasses import dataclass, replace
 from typing import List, Tuple
-
-import torch
 
 from . import graphs
 

@@ -13,7 +13,7 @@ totals of the gradient messages live in `S[l]`, one row per vertex in owner orde
 (`off[j]` = first row of partition j): difference messages only ever add to them.
 """
 import ctypes
-from dataclasses import dataclass, field
+from dataclasses import dataclass
 from typing import List
 
 import torch

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from cdfgen import configs, features, graphs
+from cdfgen import configs, features
 from helpers import assert_rows_close, bf16_to_f32, csr_np
 
 pytestmark = pytest.mark.gpu

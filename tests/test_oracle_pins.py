@@ -6,7 +6,6 @@ import os
 
 import numpy as np
 import pytest
-import torch
 
 from cdfgen import configs, features, graphs
 from helpers import (assert_rows_close, bf16_bits, bf16_to_f32, csr_dense, csr_np, dense_norm_adj)

@@ -1,6 +1,5 @@
 """Hierarchical EBV partitioner (Sec. 6): pins of the oracle, then the library's host function against
 the oracle, edge by edge. No GPU is involved anywhere in this file."""
-import numpy as np
 import pytest
 import torch
 
