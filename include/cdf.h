@@ -113,6 +113,23 @@ int cdf_cache_filter(const void* cur, const void* cached, int32_t n_rows, int32_
                      int32_t* n_sent, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * cdf_cache_filter for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc. Same
+ * arguments and results as cdf_cache_filter, minus ws / ws_bytes: the per-block counts and offsets
+ * (the only scratch the test needs) live in a static device array inside the library, about 1 MiB,
+ * one copy per GPU, held until the process ends. The call allocates and frees nothing; its first
+ * call on a device looks the array's address up (a host-side query). The device that owns the
+ * buffers must be the current device.
+ *  - n_rows above 8 388 608 (8 Mi) is rejected with CDF_ERR_UNSUPPORTED.
+ *  - Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (different
+ *    streams or threads) race; order them on one stream. The array keeps the last call's contents;
+ *    each call overwrites the part it reads, so nothing needs clearing in between.
+ */
+int cdf_cache_filter_static(const void* cur, const void* cached, int32_t n_rows, int32_t dim, int64_t ld,
+                            cdf_dtype dt, float eps, cdf_norm norm, uint8_t* mask, int32_t* idx,
+                            int32_t* n_sent, void* stream);
+
+/*
  * Message build for the listed rows (Alg. 2 "send the difference"; Sec. 5, first equation)
  * followed by the cache commit. For k < *n_sent, r = idx[k]:
  *   m = cur[r] - cached[r]  (delta != 0, the paper)   or   m = cur[r]  (delta == 0)

@@ -20,7 +20,7 @@ COMMIT_NONE, COMMIT_CUR, COMMIT_DEQ = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf_profile_kernel_name", "cdf_profile_read",
-           "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_quantize", "cdf_cache_filter_quantize",
+           "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_cache_filter_static", "cdf_quantize", "cdf_cache_filter_quantize",
            "cdf_dequantize", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
            "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd",
            "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_gather_rows", "cdf_map_index",
@@ -193,6 +193,14 @@ def cdf_cache_filter(cur, cached, eps, norm, mask, idx, n_sent, ws):
                                  ctypes.c_int(norm), _ptr(mask), _ptr(idx), _ptr(n_sent), _ptr(ws),
                                  ctypes.c_size_t(ws.numel() * ws.element_size()), _stream())
     _check("cdf_cache_filter", rc)
+
+
+def cdf_cache_filter_static(cur, cached, eps, norm, mask, idx, n_sent):
+    rc = load().cdf_cache_filter_static(_ptr(cur), _ptr(cached), ctypes.c_int32(cur.shape[0]),
+                                        ctypes.c_int32(cur.shape[1]), ctypes.c_int64(_ld(cur)),
+                                        ctypes.c_int(dtype_of(cur)), ctypes.c_float(eps), ctypes.c_int(norm),
+                                        _ptr(mask), _ptr(idx), _ptr(n_sent), _stream())
+    _check("cdf_cache_filter_static", rc)
 
 
 def cdf_quantize(cur, cached, idx, n_sent, max_sent, bits, qs, commit, delta, codes, meta):

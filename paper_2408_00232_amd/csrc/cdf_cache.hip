@@ -16,6 +16,8 @@
 // where c is the component inside the vector and a = iteration mod (4/EPV) selects
 // one of 4/EPV accumulators per lane-component. The butterfly then runs over c, the
 // lane bits and a, in that order.
+#include <mutex>
+
 #include "cdf_common.h"
 
 namespace cdf {
@@ -313,33 +315,34 @@ size_t filter_workspace_bytes(int64_t n_rows) {
 
 using namespace cdf;
 
-extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_rows, int32_t dim, int64_t ld,
-                                cdf_dtype dt, float eps, cdf_norm norm, uint8_t* mask, int32_t* idx,
-                                int32_t* n_sent, void* ws, size_t ws_bytes, void* stream) {
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  CDF_REQUIRE(n_rows >= 0 && dim > 0 && ld >= dim, "cdf_cache_filter: bad shape n_rows=%d dim=%d ld=%lld",
-              n_rows, dim, (long long)ld);
-  CDF_REQUIRE(n_sent != nullptr, "cdf_cache_filter: n_sent is null");
-  CDF_REQUIRE(eps >= 0.0f && eps <= 3.0e38f, "cdf_cache_filter: eps must be finite and >= 0");
-  if (dt != CDF_F32 && dt != CDF_BF16) CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_cache_filter: dtype %d", (int)dt);
-  if (norm != CDF_NORM_LINF && norm != CDF_NORM_L2)
-    CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_cache_filter: norm %d", (int)norm);
+// Shared body of the two cache-test entry points: argument checks, then the three launches with the
+// per-block counts and offsets in `buf` (buf_bytes available; the caller's workspace or the
+// library's own static array).
+static int cache_filter_run(const char* fn, const void* cur, const void* cached, int32_t n_rows, int32_t dim,
+                            int64_t ld, cdf_dtype dt, float eps, cdf_norm norm, uint8_t* mask, int32_t* idx,
+                            int32_t* n_sent, void* buf, size_t buf_bytes, hipStream_t st) {
+  CDF_REQUIRE(n_rows >= 0 && dim > 0 && ld >= dim, "%s: bad shape n_rows=%d dim=%d ld=%lld", fn, n_rows, dim,
+              (long long)ld);
+  CDF_REQUIRE(n_sent != nullptr, "%s: n_sent is null", fn);
+  CDF_REQUIRE(eps >= 0.0f && eps <= 3.0e38f, "%s: eps must be finite and >= 0", fn);
+  if (dt != CDF_F32 && dt != CDF_BF16) CDF_FAIL(CDF_ERR_UNSUPPORTED, "%s: dtype %d", fn, (int)dt);
+  if (norm != CDF_NORM_LINF && norm != CDF_NORM_L2) CDF_FAIL(CDF_ERR_UNSUPPORTED, "%s: norm %d", fn, (int)norm);
   if (n_rows == 0) {
     // nothing to test: the count is still defined (written by a kernel, not a memset node,
     // so that the call can be captured into a graph)
     { ProfScope ps(K_SCAN, st); scan_kernel<<<1, 1024, 0, st>>>(nullptr, 0, nullptr, n_sent); }
-    CDF_LAUNCH_CHECK("cdf_cache_filter/scan");
+    CDF_LAUNCH_CHECK("cache filter/scan");
     return CDF_OK;
   }
-  CDF_REQUIRE(cur && cached && mask && idx, "cdf_cache_filter: null pointer");
+  CDF_REQUIRE(cur && cached && mask && idx, "%s: null pointer", fn);
   const size_t esz = elem_bytes(dt);
   CDF_REQUIRE(aligned(cur, esz) && aligned(cached, esz) && aligned(idx, 4) && aligned(n_sent, 4),
-              "cdf_cache_filter: misaligned pointer");
+              "%s: misaligned pointer", fn);
   const int nblocks = static_cast<int>(ceil_div(n_rows, kRowsPerBlock));
-  if (!ws || ws_bytes < filter_workspace_bytes(n_rows) || !aligned(ws, 4))
-    CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_cache_filter: workspace too small (%zu < %zu)", ws_bytes,
+  if (!buf || buf_bytes < filter_workspace_bytes(n_rows) || !aligned(buf, 4))
+    CDF_FAIL(CDF_ERR_WORKSPACE, "%s: workspace too small (%zu < %zu)", fn, buf_bytes,
              filter_workspace_bytes(n_rows));
-  int* counts = static_cast<int*>(ws);
+  int* counts = static_cast<int*>(buf);
   int* offsets = counts + scan_stride(nblocks);
 
   const int epv = pick_epv(dim, ld, esz, cur, cached);
@@ -359,8 +362,59 @@ extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_r
   }
 #undef CDF_FILTER_CASE
   prof_end(K_FILTER, st);
-  CDF_LAUNCH_CHECK("cdf_cache_filter/filter");
+  CDF_LAUNCH_CHECK("cache filter/filter");
   return scan_and_compact(mask, n_rows, counts, offsets, idx, n_sent, st);
+}
+
+extern "C" int cdf_cache_filter(const void* cur, const void* cached, int32_t n_rows, int32_t dim, int64_t ld,
+                                cdf_dtype dt, float eps, cdf_norm norm, uint8_t* mask, int32_t* idx,
+                                int32_t* n_sent, void* ws, size_t ws_bytes, void* stream) {
+  return cache_filter_run("cdf_cache_filter", cur, cached, n_rows, dim, ld, dt, eps, norm, mask, idx, n_sent, ws,
+                          ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+// ---- the cache test for callers that cannot allocate or pass a workspace ----
+// The per-block counts and offsets live in a static device array (one copy per GPU, held until the
+// process ends). Host code never uses the array's name as an address: it asks the runtime for the
+// device address once per device and passes that to the kernels like any other buffer.
+constexpr int32_t kStaticMaxRows = 8 << 20;  // 8 Mi rows -> 131 072 blocks -> about 1 MiB of counts + offsets
+constexpr size_t kStaticScratchBytes =
+    (((static_cast<size_t>(kStaticMaxRows / kRowsPerBlock) + 1 + 3) / 4 * 4 + kStaticMaxRows / kRowsPerBlock + 1) *
+         sizeof(int) + 255) / 256 * 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+static int static_scratch(const char* fn, void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    CDF_FAIL(CDF_ERR_HIP, "%s: cannot identify the current device", fn);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) CDF_FAIL(CDF_ERR_HIP, "%s: hipGetSymbolAddress: %s", fn, hipGetErrorString(e));
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return CDF_OK;
+}
+
+extern "C" int cdf_cache_filter_static(const void* cur, const void* cached, int32_t n_rows, int32_t dim, int64_t ld,
+                                       cdf_dtype dt, float eps, cdf_norm norm, uint8_t* mask, int32_t* idx,
+                                       int32_t* n_sent, void* stream) {
+  static_assert(kStaticScratchBytes >= 256, "scratch size");
+  if (n_rows > kStaticMaxRows)
+    CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_cache_filter_static: %d rows exceed the static scratch (at most %d rows)",
+             n_rows, kStaticMaxRows);
+  void* sp = nullptr;
+  const int rc = static_scratch("cdf_cache_filter_static", &sp);
+  if (rc != CDF_OK) return rc;
+  return cache_filter_run("cdf_cache_filter_static", cur, cached, n_rows, dim, ld, dt, eps, norm, mask, idx, n_sent,
+                          sp, kStaticScratchBytes, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int cdf_active_rows(const uint8_t* flags, const int32_t* map, int32_t n_rows, uint8_t* mask, int32_t* idx,
