@@ -67,6 +67,37 @@ def gather_csr_rows(rowptr, colidx, vals, rows):
     return ptr, colidx[pos].long(), vals[pos]
 
 
+def check_gradient_messages_from_seeded_cache(orc, cdf, w, qs, norm, L, n, h, run_bwd, dfull, seed):
+    from cdfgen import rng
+    s_r = rng.uniform01(w.seed, seed, torch.arange(h, dtype=torch.int64, device=DEV)) * 2.2
+    factor = (1.0 + w.eps * s_r).float().view(-1, 1)
+    cache0 = (dfull[n:].float() * factor).to(dfull.dtype)
+    L.gcache_sent.copy_(cache0)
+    run_bwd()
+    torch.cuda.synchronize()
+    gn = int(L.gn_sent.item())
+    gmask = L.gmask[:h]
+    assert gn == int(gmask.sum().item())
+    assert torch.equal(L.gidx[:gn].long(), torch.nonzero(gmask).flatten())
+    assert 0.25 * h < gn < 0.75 * h, (gn, h)
+    # rows that were not sent keep their cache
+    assert torch.equal(L.gcache_sent[~gmask.bool()], cache0[~gmask.bool()])
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    S = torch.unique(torch.randint(0, h, (4096,), device=DEV, generator=g))
+    rows, cache = host(dfull[n:][S]), host(cache0[S])
+    omask, oidx = orc.cache_filter(rows, cache, w.eps, norm)
+    ocodes, ometa = orc.quantize(rows, cache, oidx, w.bits, qs, orc.COMMIT_CUR, True)
+    assert 0.25 * S.numel() < oidx.size < 0.75 * S.numel()
+    np.testing.assert_array_equal(host(gmask[S]), omask)
+    np.testing.assert_array_equal(host(L.gcache_sent[S]), cache)
+    sent_rows = S[torch.from_numpy(oidx).long().to(DEV)]
+    k = torch.searchsorted(L.gidx[:gn].long(), sent_rows)
+    assert torch.equal(L.gidx[:gn].long()[k], sent_rows)
+    rb = L.row_bytes
+    np.testing.assert_array_equal(host(L.gcodes[: gn * rb].view(gn, rb)[k]), ocodes)
+    np.testing.assert_array_equal(host(L.gmeta[:gn][k]), ometa)
+
+
 @pytest.mark.parametrize("name", ["share", "wide", "large"])
 def test_full_size_sampled(oracle, name):
     import paper_2408_00232_amd as cdf
@@ -178,6 +209,12 @@ def test_full_size_sampled(oracle, name):
         assert gn == int(nzrow.sum().item())
         assert torch.equal(L.gidx[:gn].long(), torch.nonzero(nzrow).flatten())
         assert torch.equal(L.gcache_sent, L.dxfull[n:] * nzrow.view(-1, 1).to(L.dxfull.dtype))
+        # ---- the same step again from a seeded, non-trivial gradient cache: every cached row is the
+        # row itself scaled by 1 + eps * s_r, s_r uniform in [0, 2.2), so the rows lie densely on both
+        # sides of the threshold. Sampled rows are redone by the oracle in lock-step (from the rows
+        # the GPU step produced and the cache it started from): decision, codes, meta, commit. ----
+        check_gradient_messages_from_seeded_cache(orc, cdf, w, qs, norm, L, n, h, lambda: cdf.cdf_gcn_layer_bwd(
+            model.bwd[li][0], model.ws), L.dxfull, 600 + li)
     del model
     torch.cuda.empty_cache()
 
@@ -259,6 +296,8 @@ def test_full_size_share_transform_first_layer(oracle):
     nzrow = (L.dtfull[n:] != 0).any(1)
     assert gn == int(nzrow.sum().item())
     assert torch.equal(L.gidx[:gn].long(), torch.nonzero(nzrow).flatten())
+    check_gradient_messages_from_seeded_cache(orc, cdf, w, orc.Q_MINMAX, orc.NORM_LINF, L, n, h,
+                                              lambda: cdf.cdf_gcn_layer_tf_bwd(model.bwd[li][0], model.ws), L.dtfull, 704)
     rs = np.random.default_rng(703)
     gdW = host(L.dW)
     scale = np.abs(gdW).max()
