@@ -5,11 +5,14 @@ A step = the whole hot path over the model of the chosen workload: for every lay
 forward step (cache test, message build, recovery, aggregation, dense transform) and the
 backward step (dense gradients, transposed aggregation, cache test and message build on the
 halo gradients). value = edges traversed per second = layers * nnz / step time, inputs
-resident in HBM. One JSON line on stdout; progress on stderr.
+resident in HBM. The headline runs every layer in the generic order (aggregate first, then
+transform); the same model with the per-layer choice of the order is timed beside it and
+reported as `optimised_order`. One JSON line on stdout; progress on stderr.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -18,6 +21,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+AGG_KERNELS = ("spmm_kernel", "spmm_sliced_kernel")
 
 
 def log(*a):
@@ -25,11 +30,53 @@ def log(*a):
 
 
 def spmm_bytes(rows_out, rows_in, nnz, dim, esz):
-    """Algorithmic bytes of one aggregation launch: the CSR arrays, every needed input row once,
-    every output row once (compulsory traffic), and the same with no reuse of input rows."""
+    """Bytes of one aggregation launch under two models: every needed input row read once
+    (compulsory traffic), and one input row read per stored entry (no reuse at all: what the
+    caches see). Both include the CSR arrays and the output rows."""
     csr = 8 * (rows_out + 1) + 8 * nnz
     out = rows_out * dim * esz
     return csr + out + rows_in * dim * esz, csr + out + nnz * dim * esz
+
+
+def read_traffic(workload, order, kernels_sha):
+    """profiles/traffic_<workload>.txt: per-launch FETCH_SIZE / WRITE_SIZE bytes of every kernel, from the
+    two rocprofv3 --pmc runs of this same script. -> (dict kernel -> bytes, info) or (None, info)."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    info = {"file": os.path.relpath(path, ROOT), "present": os.path.exists(path)}
+    if not info["present"]:
+        return None, info
+    per = {}
+    for line in open(path):
+        line = line.strip()
+        if line.startswith("#"):
+            for key in ("kernels_sha", "order", "commit"):
+                tag = key + "="
+                if tag in line:
+                    info[key] = line.split(tag)[1].split()[0]
+            continue
+        if "=" in line:
+            name, rest = line.split("=")
+            f_b, w_b = rest.split()[:2]
+            per[name.strip()] = float(f_b) + float(w_b)
+    info["stale"] = info.get("kernels_sha") != kernels_sha
+    info["same_order"] = info.get("order") == order
+    return per, info
+
+
+def time_steps(model, first, steps):
+    """`steps` steps bracketed by synchronisation: -> (wall seconds, [ms of every step from events
+    recorded on the launch stream])."""
+    import torch
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        ev[i].record()
+        model.step(first + i)
+    ev[steps].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    return elapsed, [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
 
 
 def cpu_baseline(model, budget_edges=12_000_000):
@@ -133,16 +180,153 @@ def cpu_baseline(model, budget_edges=12_000_000):
                       f"{nnz_s} edges, all {nl} layers fwd+bwd, one stationary step in {dt:.2f} s"}
 
 
+def kernel_report(cdf, model, w, steps):
+    """Per-kernel durations from the events the library recorded inside the timed region, the
+    aggregation launches by their position in a step, and every kernel against its own roof."""
+    seq = cdf.cdf_profile_read_all()
+    kernels = {}
+    for name, ms in seq:
+        kernels.setdefault(name, []).append(ms)
+    esz = 2 if w.dtype == "bf16" else 4
+    n, h, nnz = model.n_loc, model.n_halo, model.nnz
+    widths = model.spmm_widths()
+    # launch order of the aggregations within a step: forward layers 0..L-1 on A, then backward
+    # layers L-1..0 on A^T (the library records which of its two aggregation kernels ran)
+    per_step = [spmm_bytes(n, n + h, nnz, f, esz) for f in widths] + \
+               [spmm_bytes(n + h, n, nnz, f, esz) for f in reversed(widths)]
+    wid_of = list(widths) + list(reversed(widths))
+    agg = [(name, ms) for name, ms in seq if name in AGG_KERNELS]
+    nl = len(per_step)
+    positions = None
+    if len(agg) == nl * steps:
+        positions = []
+        for i in range(nl):
+            mine = agg[i::nl]
+            assert len({name for name, _ in mine}) == 1
+            positions.append({"kernel": mine[0][0], "width": wid_of[i], "matrix": "A" if i < nl // 2 else "A^T",
+                              "avg_ms": sum(ms for _, ms in mine) / len(mine),
+                              "no_reuse_bytes": per_step[i][1], "compulsory_bytes": per_step[i][0]})
+    out = {name: {"launches": len(ms), "avg_ms": sum(ms) / len(ms), "ms_per_step": sum(ms) / steps}
+           for name, ms in kernels.items()}
+    return out, positions
+
+
+def roofline(positions, traffic, tinfo):
+    """The dominant kernel (the aggregation variant with the most time per step) against the HBM roof.
+    achieved = bytes the hardware counters saw this kernel move per launch (FETCH_SIZE + WRITE_SIZE at the
+    L2 <-> fabric interface, from the committed rocprofv3 runs of this script) / its average launch time
+    measured here. The byte models are side figures: `l2_level` counts one feature row per stored entry
+    (what the caches serve, can exceed the HBM peak), `compulsory` counts every input row once."""
+    if not positions:
+        return None
+    by_kernel = {}
+    for p in positions:
+        by_kernel.setdefault(p["kernel"], []).append(p)
+    name = max(by_kernel, key=lambda k: sum(p["avg_ms"] for p in by_kernel[k]))
+    sel = by_kernel[name]
+    avg_s = sum(p["avg_ms"] for p in sel) / len(sel) / 1e3
+    bmax = sum(p["no_reuse_bytes"] for p in sel) / len(sel)
+    bmin = sum(p["compulsory_bytes"] for p in sel) / len(sel)
+    r = {"kernel": name, "bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+         "traffic": None, "avg_launch_ms": avg_s * 1e3, "launches_per_step": len(sel),
+         "l2_level_bytes_per_launch": bmax, "l2_level_GBps": bmax / avg_s / 1e9,
+         "compulsory_bytes_per_launch": bmin, "compulsory_GBps": bmin / avg_s / 1e9,
+         "compulsory_frac": bmin / avg_s / 1e9 / HBM_PEAK_GBS, "traffic_over_compulsory": None,
+         "traffic_source": tinfo}
+    usable = traffic is not None and name in traffic and tinfo.get("same_order")
+    if usable:
+        t = traffic[name]
+        r["traffic"] = t
+        r["achieved"] = t / avg_s / 1e9
+        r["frac"] = r["achieved"] / HBM_PEAK_GBS
+        r["traffic_over_compulsory"] = t / bmin
+        if tinfo.get("stale"):
+            log(f"[bench] WARNING: {tinfo['file']} was taken on other kernel sources "
+                f"({tinfo.get('kernels_sha')}); roofline.traffic may be out of date")
+    else:
+        log(f"[bench] no usable counter summary for this workload / order ({tinfo}); roofline.frac is null")
+    return r
+
+
+def kernel_rooflines(model, w, kernels):
+    """Every HBM-bound kernel against its own algorithmic bytes (streaming kernels: these are the bytes
+    that must move), every dense kernel against the peak of the matrix instruction it executes."""
+    esz = 2 if w.dtype == "bf16" else 4
+    n, h = model.n_loc, model.n_halo
+    widths = model.spmm_widths()
+
+    def avg(xs):
+        return sum(xs) / len(xs)
+    lay = list(zip(widths, [g for _, g in w.layers()]))   # (width of the halo rows, f_out)
+    sent_f = [int(L.n_sent.item()) for L in model.layers]
+    sent_b = [int(L.gn_sent.item()) for L in model.layers]
+    rb = [L.row_bytes for L in model.layers]
+    alg = {
+        "filter_kernel": avg([h * (2 * f * esz + 1) + 4 * sn[i] for sn in (sent_f, sent_b) for i, (f, _) in enumerate(lay)]),
+        "quantize_kernel": avg([sn[i] * (3 * f * esz + rb[i] + 12) for sn in (sent_f, sent_b) for i, (f, _) in enumerate(lay)]),
+        "dequantize_kernel": avg([sent_f[i] * (2 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)]),
+        # one-pass test + message build: every row read once, sent rows committed and coded
+        "test_encode_kernel": avg([h * (2 * f * esz + 1) + sn[i] * (f * esz + rb[i] + 8)
+                                   for sn in (sent_f, sent_b) for i, (f, _) in enumerate(lay)]),
+        "gather_codes_kernel": avg([sn[i] * (2 * rb[i] + 16 + 4)
+                                    for sn in (sent_f, sent_b) for i, (f, _) in enumerate(lay)]),
+    }
+    per_kernel = {}
+    for name, b in alg.items():
+        if name in kernels:
+            gbs = b / (kernels[name]["avg_ms"] * 1e-3) / 1e9
+            per_kernel[name] = {"bound": "hbm", "algorithmic_bytes_per_launch": b, "achieved_GBps": gbs,
+                                "peak_GBps": HBM_PEAK_GBS, "frac": gbs / HBM_PEAK_GBS}
+    flops = avg([2.0 * n * f * g for f, g in w.layers()])
+    # bf16-stored activations: the forward product and dM run on the bf16 matrix cores with fp32
+    # operands split into a high and a low part (2 and 3 products executed per useful one); dW, and
+    # everything of an fp32 workload, runs on the fp32 matrix cores
+    executed = {"gemm_kernel<FWD>": 2, "gemm_kernel<DM>": 3} if w.dtype == "bf16" else {}
+    for name in ("gemm_kernel<FWD>", "gemm_kernel<DW>", "gemm_kernel<DM>"):
+        if name in kernels:
+            mult = executed.get(name, 1)
+            peak = MFMA_PEAK_TFLOPS["bf16" if mult > 1 else "f32"]
+            tf = flops / (kernels[name]["avg_ms"] * 1e-3) / 1e12
+            per_kernel[name] = {"bound": "mfma", "instruction": "bf16" if mult > 1 else "f32",
+                                "useful_flops_per_launch": flops, "useful_TFLOPs": tf,
+                                "executed_TFLOPs": tf * mult, "peak_TFLOPs": peak, "frac": tf * mult / peak}
+    return per_kernel
+
+
+def run_order(cdf, w, P, dev, order, rho, phi, warmup, steps, profile):
+    """Build the model in one order of the products, warm up, time `steps` steps."""
+    import torch
+    from paper_2408_00232_amd.workload import Model
+    model = Model(w, dev, rho=rho, phi=phi, partition=P, order=order)
+    for t in range(warmup):
+        model.step(t)
+    torch.cuda.synchronize()
+    if profile:
+        cdf.cdf_profile_enable(True)
+    elapsed, step_ms = time_steps(model, warmup, steps)
+    if profile:
+        cdf.cdf_profile_enable(False)
+    res = {"ms_per_step": elapsed / steps * 1e3, "ms_per_step_median": statistics.median(step_ms),
+           "per_kernel_events": bool(profile),
+           "value": model.edges_per_step() / (elapsed / steps) / 1e9,
+           "value_median": model.edges_per_step() / (statistics.median(step_ms) * 1e-3) / 1e9,
+           "order_per_layer": ["transform-first" if t else "aggregate-first" for t in model.tf]}
+    return model, res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="share", help="tiny | mid | large | wide | share")
-    ap.add_argument("--rho", type=float, default=0.37, help="fraction of halo rows refreshed per step")
+    ap.add_argument("--rho", type=float, default=0.37, help="fraction of halo rows refreshed per step (imposed by the inputs)")
     ap.add_argument("--phi", type=float, default=0.01, help="fraction of local rows whose gradient changes")
-    ap.add_argument("--order", default="auto", choices=["auto", "aggregate"],
-                    help="auto: layers with f_out < f_in compute A (X W); aggregate: every layer computes (A X) W")
+    ap.add_argument("--order", default="aggregate", choices=["aggregate", "auto"],
+                    help="aggregate: every layer computes (A X) W, the generic layer step (headline); "
+                         "auto: layers with f_out < f_in compute A (X W)")
+    ap.add_argument("--no-optimised", action="store_true", help="skip the second timing in the other order")
+    ap.add_argument("--no-rho-sweep", action="store_true", help="skip the timings at other send fractions")
     ap.add_argument("--graph", action="store_true",
                     help="also time the same steps replayed from captured HIP graphs (reported beside the eager figures)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -156,7 +340,7 @@ def main():
     import torch
     from cdfgen import configs
     import paper_2408_00232_amd as cdf
-    from paper_2408_00232_amd.workload import Model
+    from paper_2408_00232_amd import build as cdf_build
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     cdf.binding.load()
@@ -164,12 +348,7 @@ def main():
     w = configs.ALL[args.workload]
     t_setup = time.time()
     log(f"[bench] building workload '{w.name}' on {dev} ...")
-    model = Model(w, dev, rho=args.rho, phi=args.phi, order=args.order)
-    torch.cuda.synchronize()
-    log(f"[bench] partition: n_loc={model.n_loc} n_halo={model.n_halo} nnz={model.nnz} "
-        f"layers={w.layers()} setup {time.time() - t_setup:.1f}s "
-        f"mem {torch.cuda.memory_allocated() / 2**30:.1f} GiB")
-
+    P = configs.build_partition(w, device=dev)
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.zeros_like(src)
@@ -177,28 +356,27 @@ def main():
             cdf.cdf_profile_copy(dst, src)
         torch.cuda.synchronize()
         del src, dst
-    for t in range(args.warmup):
-        model.step(t)
-    torch.cuda.synchronize()
-    log("[bench] warmup done")
+    model, head = run_order(cdf, w, P, dev, args.order, args.rho, args.phi, args.warmup, args.steps, profile=True)
+    log(f"[bench] partition: n_loc={model.n_loc} n_halo={model.n_halo} nnz={model.nnz} layers={w.layers()} "
+        f"order={args.order} setup+run {time.time() - t_setup:.1f}s mem {torch.cuda.memory_allocated() / 2**30:.1f} GiB")
+    log(f"[bench] {head['ms_per_step']:.3f} ms/step (median {head['ms_per_step_median']:.3f}) = {head['value']:.3f} GE/s")
 
-    cdf.cdf_profile_enable(True)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(args.warmup, args.warmup + args.steps):
-        model.step(t)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    cdf.cdf_profile_enable(False)
+    kernels, positions = kernel_report(cdf, model, w, args.steps)
+    # the same steps once more without the library's per-kernel events (two event records per launch
+    # cost nothing on millisecond kernels and up to half of a launch-bound step)
+    e2, ms2 = time_steps(model, args.warmup + args.steps, args.steps)
+    head["ms_per_step_without_kernel_events"] = statistics.median(ms2)
+    head["value_without_kernel_events"] = model.edges_per_step() / (statistics.median(ms2) * 1e-3) / 1e9
+    log(f"[bench] without per-kernel events: {head['ms_per_step_without_kernel_events']:.3f} ms/step")
+    traffic, tinfo = read_traffic(w.name, args.order, cdf_build.sources_sha())
+    roof = roofline(positions, traffic, tinfo)
+    per_kernel = kernel_rooflines(model, w, kernels)
 
-    ms_per_step = elapsed / args.steps * 1e3
-    ges = model.edges_per_step() / (elapsed / args.steps) / 1e9
-
-    # per layer shape: forward and backward time of the generic layer step (a separate, untimed pass
-    # of the same steps with an event pair around every layer call), median over the passes
-    import statistics
+    # per layer shape: forward and backward time of the layer step (a separate, untimed pass of the
+    # same steps with an event pair around every layer call), median over the passes
     fw, bw = [], []
-    for t in range(args.warmup + args.steps, args.warmup + args.steps + max(4, min(args.steps, 10))):
+    t_next = args.warmup + 2 * args.steps
+    for t in range(t_next, t_next + max(4, min(args.steps, 10))):
         a_ms, b_ms = model.step_timed_per_layer(t)
         fw.append(a_ms)
         bw.append(b_ms)
@@ -213,109 +391,23 @@ def main():
     if args.graph:
         # launch-bound workloads (tiny, mid): the same steps as two captured graphs, one per input version
         model.capture()
-        t_next = args.warmup + args.steps
+        t_next += 12
         for t in range(t_next, t_next + 2):
             model.step(t)
-        torch.cuda.synchronize()
-        tg = time.perf_counter()
-        for t in range(t_next + 2, t_next + 2 + args.steps):
-            model.step(t)
-        torch.cuda.synchronize()
-        eg = time.perf_counter() - tg
-        graph_replay = {"ms_per_step": eg / args.steps * 1e3, "value": model.edges_per_step() / (eg / args.steps) / 1e9,
-                        "unit": "GE/s"}
+        eg, g_ms = time_steps(model, t_next + 2, args.steps)
+        graph_replay = {"ms_per_step": eg / args.steps * 1e3, "ms_per_step_median": statistics.median(g_ms),
+                        "value": model.edges_per_step() / (eg / args.steps) / 1e9, "unit": "GE/s"}
 
-    # per-kernel durations from the events recorded inside the timed region
-    kernels = {}
-    for k in range(cdf.cdf_profile_kernels()):
-        ms = cdf.cdf_profile_read(k)
-        if ms:
-            name = cdf.cdf_profile_kernel_name(k)
-            kernels[name] = {"launches": len(ms), "avg_ms": sum(ms) / len(ms),
-                             "ms_per_step": sum(ms) / args.steps, "_ms": ms}
-    # dominant kernel: the aggregation. Launch order within a step: forward layers 0..L-1 on A,
-    # then backward layers L-1..0 on A^T; algorithmic bytes differ per launch (feature width).
-    esz = 2 if w.dtype == "bf16" else 4
+    rho_f = [int(L.n_sent.item()) / max(model.n_halo, 1) for L in model.layers]
+    rho_b = [int(L.gn_sent.item()) / max(model.n_halo, 1) for L in model.layers]
     n, h, nnz = model.n_loc, model.n_halo, model.nnz
-    widths = model.spmm_widths()
-    per_step = [spmm_bytes(n, n + h, nnz, f, esz) for f in widths] + \
-               [spmm_bytes(n + h, n, nnz, f, esz) for f in reversed(widths)]
-    nl = len(per_step)
-    # which launch of a step runs which aggregation kernel (the library slices the columns when the
-    # width is a whole number of 128-byte lines and rows average 8+ entries)
-    line = 64 if w.dtype == "bf16" else 32
-    rows_of = [n] * len(widths) + [n + h] * len(widths)
-    wid_of = list(widths) + list(reversed(widths))
-    kern_of = ["spmm_sliced_kernel" if wd % line == 0 and nnz >= 8 * r else "spmm_kernel"
-               for wd, r in zip(wid_of, rows_of)]
-    times = {k: list(kernels[k]["_ms"]) for k in ("spmm_kernel", "spmm_sliced_kernel") if k in kernels}
-    pos_ms = [[] for _ in range(nl)]
-    ok = all(sum(1 for k in kern_of if k == name) * args.steps == len(ms) for name, ms in times.items())
-    if ok:
-        cursor = {k: 0 for k in times}
-        for _ in range(args.steps):
-            for i, k in enumerate(kern_of):
-                pos_ms[i].append(times[k][cursor[k]])
-                cursor[k] += 1
-    roof = None
-    if ok and all(pos_ms):
-        spmm_name = max(times, key=lambda k: sum(times[k]))
-        sel = [i for i, k in enumerate(kern_of) if k == spmm_name]
-        bmin = sum(per_step[i][0] for i in sel) / len(sel)
-        bmax = sum(per_step[i][1] for i in sel) / len(sel)
-        avg_s = sum(times[spmm_name]) / len(times[spmm_name]) / 1e3
-        # achieved: the aggregation's algorithmic bytes - per stored entry 8 bytes of CSR plus one
-        # feature row (dim * element size), plus row pointers and the output rows - over the
-        # average launch time. compulsory_*: the same with every input row counted once only.
-        roof = {"kernel": spmm_name, "bound": "hbm", "achieved": bmax / avg_s / 1e9, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": bmax / avg_s / 1e9 / HBM_PEAK_GBS, "traffic": None,
-                "avg_launch_ms": avg_s * 1e3, "algorithmic_bytes_per_launch": bmax,
-                "compulsory_bytes_per_launch": bmin, "compulsory_GBps": bmin / avg_s / 1e9,
-                "launches_per_step": len(sel),
-                "aggregation_ms_by_position": [sum(x) / len(x) for x in pos_ms],
-                "aggregation_kernel_by_position": kern_of,
-                "aggregation_width_by_position": wid_of,
-                "algorithmic_GBps_by_position": [per_step[i][1] / (sum(pos_ms[i]) / len(pos_ms[i])) / 1e6
-                                                 for i in range(nl)]}
-        tfile = os.path.join(ROOT, "profiles", f"traffic_{w.name}.txt")
-        if os.path.exists(tfile):
-            for line in open(tfile):
-                if line.startswith(spmm_name + " ="):
-                    f_b, w_b = line.split("=")[1].split()
-                    roof["traffic"] = float(f_b) + float(w_b)
+    edges = model.edges_per_step()
 
-    # every HBM-bound kernel against its own algorithmic bytes, every dense kernel against the fp32
-    # matrix-core peak (per-launch averages over the timed region; widths differ between layers)
-    def avg(xs):
-        return sum(xs) / len(xs)
-    lay = [(f, g) for f, g in zip(widths, [g for _, g in w.layers()])]   # (width of the halo rows, f_out)
-    sent_f = [int(L.n_sent.item()) for L in model.layers]
-    sent_b = [int(L.gn_sent.item()) for L in model.layers]
-    rb = [L.row_bytes for L in model.layers]
-    alg = {
-        "filter_kernel": avg([h * (2 * f * esz + 1) + 4 * sent_f[i] for i, (f, _) in enumerate(lay)] +
-                             [h * (2 * f * esz + 1) + 4 * sent_b[i] for i, (f, _) in enumerate(lay)]),
-        "quantize_kernel": avg([sent_f[i] * (3 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)] +
-                               [sent_b[i] * (3 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)]),
-        "dequantize_kernel": avg([sent_f[i] * (2 * f * esz + rb[i] + 12) for i, (f, _) in enumerate(lay)]),
-        # one-pass test + message build: every row read once, sent rows committed and coded
-        "test_encode_kernel": avg([h * (2 * f * esz + 1) + sn[i] * (f * esz + rb[i] + 8)
-                                   for sn in (sent_f, sent_b) for i, (f, _) in enumerate(lay)]),
-        "gather_codes_kernel": avg([sn[i] * (2 * rb[i] + 16 + 4)
-                                    for sn in (sent_f, sent_b) for i, (f, _) in enumerate(lay)]),
-    }
-    flops = avg([2.0 * n * f * g for f, g in w.layers()])
-    per_kernel = {}
-    for name, b in alg.items():
-        if name in kernels:
-            gbs = b / (kernels[name]["avg_ms"] * 1e-3) / 1e9
-            per_kernel[name] = {"bound": "hbm", "algorithmic_bytes_per_launch": b, "achieved_GBps": gbs,
-                                "frac": gbs / HBM_PEAK_GBS}
-    for name in ("gemm_kernel<FWD>", "gemm_kernel<DW>", "gemm_kernel<DM>"):
-        if name in kernels:
-            tf = flops / (kernels[name]["avg_ms"] * 1e-3) / 1e12
-            per_kernel[name] = {"bound": "mfma", "flops_per_launch": flops, "achieved_TFLOPs": tf,
-                                "frac": tf / 157.3}
+    cpu = None
+    if not args.no_cpu_baseline:
+        log("[bench] timing the CPU oracle on a sample ...")
+        cpu = cpu_baseline(model)
+
     # measured streaming ceiling: the library's plain copy kernel on 1 GiB (read + write bytes)
     src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
     dst = torch.zeros_like(src)
@@ -328,33 +420,59 @@ def main():
     copy_gbs = 10 * 2 * (1 << 30) / (time.perf_counter() - tc) / 1e9
     del src, dst
 
-    rho_f = [int(L.n_sent.item()) / max(h, 1) for L in model.layers]
-    rho_b = [int(L.gn_sent.item()) / max(h, 1) for L in model.layers]
+    # the same workload at other send fractions, and in the other order of the products
+    del model
+    torch.cuda.empty_cache()
+    sweep = None
+    if not args.no_rho_sweep:
+        sweep = [{"rho": args.rho, "ms_per_step": head["ms_per_step_median"], "value": head["value_median"]}]
+        for rho in (0.05, 1.0):
+            m2, r2 = run_order(cdf, w, P, dev, args.order, rho, args.phi, 3, max(4, args.steps // 2), profile=False)
+            sweep.append({"rho": rho, "ms_per_step": r2["ms_per_step_median"], "value": r2["value_median"]})
+            del m2
+            torch.cuda.empty_cache()
+        sweep.sort(key=lambda x: x["rho"])
+    optimised = None
+    if not args.no_optimised:
+        other = "auto" if args.order == "aggregate" else "aggregate"
+        m2, optimised = run_order(cdf, w, P, dev, other, args.rho, args.phi, args.warmup, args.steps, profile=False)
+        optimised["order"] = other
+        optimised["unit"] = "GE/s"
+        optimised["note"] = ("layers whose output is narrower than their input compute A (X W): same layer, same "
+                             "steps, narrower rows in the messages and in the aggregation"
+                             if other == "auto" else "every layer computes (A X) W")
+        log(f"[bench] order={other}: {optimised['ms_per_step']:.3f} ms/step = {optimised['value']:.3f} GE/s")
+        del m2
+        torch.cuda.empty_cache()
 
-    for v in kernels.values():
-        v.pop("_ms", None)
     out = {
         "metric": "GCN layer fwd+bwd edges/sec (GE/s) per partition; % of HBM roofline",
-        "value": ges, "unit": "GE/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "value": head["value"], "unit": "GE/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
+        "ms_per_step_median": head["ms_per_step_median"], "value_median": head["value_median"],
+        "ms_per_step_without_kernel_events": head["ms_per_step_without_kernel_events"],
+        "value_without_kernel_events": head["value_without_kernel_events"],
         "config": {"workload": f"{w.name}: {w.kind} graph, {w.n_vertices} vertices, partition {w.part} of "
                                f"{w.parts} ({w.partitioner}), n_loc={n}, n_halo={h}, nnz={nnz}, layers "
                                f"{'-'.join(str(d) for d in w.dims)}, {w.bits}-bit {w.qscheme} messages, "
                                f"eps={w.eps} ({w.norm})",
-                   "order_per_layer": ["transform-first" if t else "aggregate-first" for t in model.tf],
-                   "edges_per_step": model.edges_per_step(), "send_fraction_fwd": rho_f,
-                   "send_fraction_bwd": rho_b},
+                   "order": args.order, "order_per_layer": head["order_per_layer"],
+                   "edges_per_step": edges,
+                   "send_fraction": {"imposed_by_inputs": True, "rho": args.rho, "phi": args.phi,
+                                     "fwd": rho_f, "bwd": rho_b}},
         "roofline": roof,
+        "cpu_baseline": cpu,
+        "optimised_order": optimised,
+        "rho_sweep": sweep,
+        "aggregation_by_position": positions,
         "kernels": kernels,
         "kernel_rooflines": per_kernel,
         "per_layer": per_layer,
         "copy_ceiling_GBps": copy_gbs,
         "graph_replay": graph_replay,
+        "kernels_sha": cdf_build.sources_sha(),
     }
-    if not args.no_cpu_baseline:
-        log("[bench] timing the CPU oracle on a sample ...")
-        out["cpu_baseline"] = cpu_baseline(model)
     print(json.dumps(out), flush=True)
 
 

@@ -62,6 +62,7 @@ typedef struct {
   const int64_t* rowptr; /* [n_rows + 1], rowptr[0] = 0, rowptr[n_rows] = nnz */
   const int32_t* colidx; /* [nnz], each in [0, n_cols) */
   const float* vals;     /* [nnz] */
+  const int32_t* plan;   /* NULL, or the table cdf_spmm_plan built for exactly these row pointers */
 } cdf_csr;
 
 /* Host-side text of the last error raised on the calling thread ("" if none). */
@@ -80,6 +81,9 @@ int cdf_profile_enable(int on);
 int cdf_profile_kernels(void);
 const char* cdf_profile_kernel_name(int kernel);
 int cdf_profile_read(int kernel, float* ms /* host */, int cap);
+/* All recorded launches in launch order: kernel id and duration (ms) of launch i go to the HOST arrays
+ * kernel[i], ms[i] for i < cap (either may be NULL); returns the number recorded or a negative status. */
+int cdf_profile_read_all(int32_t* kernel /* host */, float* ms /* host */, int cap);
 
 /* A plain device-to-device copy kernel (16 bytes per lane, grid-stride) of `bytes` bytes
  * (multiple of 16, both pointers 16-byte aligned). It exists so that hardware counter
@@ -177,6 +181,17 @@ int cdf_cache_filter_quantize(const void* cur, void* cached, int32_t n_rows, int
                               cdf_dtype dt, float eps, cdf_norm norm, int bits, cdf_qscheme qs,
                               cdf_commit commit, int delta, uint8_t* mask, int32_t* idx, int32_t* n_sent,
                               uint8_t* codes, float* meta, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Work split of the aggregation, computed once per matrix (the adjacency of a partition never changes
+ * during training, Sec. 3.1): the aggregation kernels cut the stored entries into equal chunks, one per
+ * wavefront, and need the row in which each chunk starts. With A->plan == NULL every cdf_spmm_* call
+ * (and every layer step) recomputes that table in its workspace; cdf_spmm_plan writes it to the caller's
+ * buffer `plan` (device memory, cdf_spmm_plan_bytes(A->nnz) bytes, 4-byte aligned) so that the caller can
+ * store the pointer in A->plan and skip that launch from then on. The table depends on rowptr and nnz only.
+ */
+size_t cdf_spmm_plan_bytes(int64_t nnz);
+int cdf_spmm_plan(const cdf_csr* A /* host */, int32_t* plan, size_t plan_bytes, void* stream);
 
 /*
  * Aggregation over the normalised adjacency (Sec. 3.1, the product A^_i H of the forward

@@ -19,9 +19,9 @@ Q_MINMAX, Q_SYMMETRIC, Q_NONE = 0, 1, 2
 COMMIT_NONE, COMMIT_CUR, COMMIT_DEQ = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
-EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf_profile_kernel_name", "cdf_profile_read",
+EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf_profile_kernel_name", "cdf_profile_read", "cdf_profile_read_all",
            "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_cache_filter_static", "cdf_quantize", "cdf_cache_filter_quantize",
-           "cdf_dequantize", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
+           "cdf_dequantize", "cdf_spmm_plan_bytes", "cdf_spmm_plan", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
            "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd",
            "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_gather_rows", "cdf_map_index",
            "cdf_mark_rows", "cdf_active_rows", "cdf_relu_fwd",
@@ -36,7 +36,8 @@ class CdfError(RuntimeError):
 
 class cdf_csr(ctypes.Structure):
     _fields_ = [("n_rows", ctypes.c_int32), ("n_cols", ctypes.c_int32), ("nnz", ctypes.c_int64),
-                ("rowptr", ctypes.c_void_p), ("colidx", ctypes.c_void_p), ("vals", ctypes.c_void_p)]
+                ("rowptr", ctypes.c_void_p), ("colidx", ctypes.c_void_p), ("vals", ctypes.c_void_p),
+                ("plan", ctypes.c_void_p)]
 
 
 class cdf_layer_fwd_args(ctypes.Structure):
@@ -109,6 +110,8 @@ def load():
         lib.cdf_workspace_bytes.restype = ctypes.c_size_t
         lib.cdf_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int64]
         lib.cdf_code_row_bytes.restype = ctypes.c_size_t
+        lib.cdf_spmm_plan_bytes.restype = ctypes.c_size_t
+        lib.cdf_spmm_plan_bytes.argtypes = [ctypes.c_int64]
         lib.cdf_code_row_bytes.argtypes = [ctypes.c_int32, ctypes.c_int, ctypes.c_int]
         lib.cdf_profile_kernel_name.restype = ctypes.c_char_p
         lib.cdf_eps_update.restype = ctypes.c_float
@@ -149,7 +152,20 @@ def make_csr(n_rows, n_cols, rowptr, colidx, vals) -> cdf_csr:
     """Host struct of device arrays (the tensors must outlive its use)."""
     assert rowptr.dtype == torch.int64 and colidx.dtype == torch.int32 and vals.dtype == torch.float32
     assert rowptr.numel() == n_rows + 1
-    return cdf_csr(n_rows, n_cols, colidx.numel(), rowptr.data_ptr(), colidx.data_ptr(), vals.data_ptr())
+    return cdf_csr(n_rows, n_cols, colidx.numel(), rowptr.data_ptr(), colidx.data_ptr(), vals.data_ptr(), None)
+
+
+def cdf_spmm_plan_bytes(nnz: int) -> int:
+    return int(load().cdf_spmm_plan_bytes(nnz))
+
+
+def cdf_spmm_plan(A: cdf_csr, plan) -> None:
+    """Fills `plan` (int32 device tensor of cdf_spmm_plan_bytes(A.nnz) bytes or more) and stores its
+    address in A.plan; the tensor must outlive A's use."""
+    assert plan.is_cuda and plan.dtype == torch.int32
+    rc = load().cdf_spmm_plan(ctypes.byref(A), _ptr(plan), ctypes.c_size_t(plan.numel() * 4), _stream())
+    _check("cdf_spmm_plan", rc)
+    A.plan = plan.data_ptr()
 
 
 def cdf_profile_enable(on: bool) -> None:
@@ -171,6 +187,17 @@ def cdf_profile_read(kernel: int, cap: int = 8192):
     if n < 0:
         _check("cdf_profile_read", n)
     return [buf[i] for i in range(min(n, cap))]
+
+
+def cdf_profile_read_all(cap: int = 8192):
+    """[(kernel name, ms)] of every recorded launch, in launch order."""
+    ids = (ctypes.c_int32 * cap)()
+    ms = (ctypes.c_float * cap)()
+    n = load().cdf_profile_read_all(ids, ms, ctypes.c_int(cap))
+    if n < 0:
+        _check("cdf_profile_read_all", n)
+    names = [cdf_profile_kernel_name(k) for k in range(cdf_profile_kernels())]
+    return [(names[ids[i]], ms[i]) for i in range(min(n, cap))]
 
 
 def cdf_profile_copy(dst, src) -> None:

@@ -6,6 +6,7 @@
 //                       block of kRowsPerBlock rows                     (HBM bound)
 //   2. scan_kernel    - one block: exclusive scan of the block counts, total -> n_sent
 //   3. compact_kernel - block b ranks its mask bytes and writes idx ascending
+// (2 and 3 are one launch, scan_compact_kernel, for inputs of up to 131 072 rows)
 //
 // Lane mapping. A row is read as vectors of EPV elements (16 bytes for fp32 when
 // alignment allows). Rows with at most 64 vectors are handled by groups of
@@ -258,6 +259,48 @@ __global__ __launch_bounds__(kRowsPerBlock) void compact_kernel(const uint8_t* _
   if (on) idx[base + __popcll(b & ((1ull << lane) - 1ull))] = row;
 }
 
+// Scan and compaction in one launch for inputs of at most kFusedBlocks blocks of kRowsPerBlock rows
+// (one pass of the scan): the offsets stay in LDS and the 16 wavefronts then rank the mask bytes of
+// blocks w, w + 16, ... exactly as compact_kernel does. Same results, one launch less.
+constexpr int kFusedBlocks = 2048;
+static_assert(kFusedBlocks <= kScanPass, "the fused kernel scans in one pass");
+
+__global__ __launch_bounds__(1024) void scan_compact_kernel(const int* __restrict__ counts, int nblocks,
+                                                            const uint8_t* __restrict__ mask, int n_rows,
+                                                            int* __restrict__ idx, int* __restrict__ total) {
+  static_assert(kRowsPerBlock == 64, "one wavefront ranks one block of rows");
+  __shared__ int wsum[16];
+  __shared__ int offs[kFusedBlocks];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int i0 = threadIdx.x * kScanPer;
+  int v[kScanPer];
+#pragma unroll
+  for (int j = 0; j < kScanPer; ++j) v[j] = i0 + j < nblocks ? counts[i0 + j] : 0;
+  int carry = 0;
+  int run = scan_pass(v, wsum, carry);
+#pragma unroll
+  for (int j = 0; j < kScanPer; ++j) {
+    if (i0 + j < nblocks) offs[i0 + j] = run;
+    run += v[j];
+  }
+  if (threadIdx.x == 0) *total = carry;
+  __syncthreads();
+  // four blocks per trip, their mask bytes requested together (the loads are what a trip waits for)
+  for (int b0 = wave; b0 < nblocks; b0 += 64) {
+    bool on[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int row = (b0 + 16 * q) * kRowsPerBlock + lane;
+      on[q] = b0 + 16 * q < nblocks && row < n_rows && mask[row] != 0;
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const unsigned long long bal = __ballot(on[q]);
+      if (on[q]) idx[offs[b0 + 16 * q] + __popcll(bal & ((1ull << lane) - 1ull))] = (b0 + 16 * q) * kRowsPerBlock + lane;
+    }
+  }
+}
+
 // mask[r] = flags[map[r]] != 0 for a block of kRowsPerBlock rows, plus the block's count.
 __global__ __launch_bounds__(kRowsPerBlock) void flag_mask_kernel(const uint8_t* __restrict__ flags,
                                                                   const int* __restrict__ map, int n_rows,
@@ -296,6 +339,11 @@ static void launch_filter(const void* cur, const void* cached, int n_rows, int d
 int scan_and_compact(const uint8_t* mask, int n_rows, int* counts, int* offsets, int32_t* idx, int32_t* n_sent,
                      hipStream_t st) {
   const int nblocks = static_cast<int>(ceil_div(n_rows, kRowsPerBlock));
+  if (nblocks > 0 && nblocks <= kFusedBlocks) {
+    { ProfScope ps(K_SCAN, st); scan_compact_kernel<<<1, 1024, 0, st>>>(counts, nblocks, mask, n_rows, idx, n_sent); }
+    CDF_LAUNCH_CHECK("scan + compact");
+    return CDF_OK;
+  }
   { ProfScope ps(K_SCAN, st); scan_kernel<<<1, 1024, 0, st>>>(counts, nblocks, offsets, n_sent); }
   CDF_LAUNCH_CHECK("scan");
   if (nblocks > 0) {

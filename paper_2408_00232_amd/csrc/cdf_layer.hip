@@ -135,6 +135,18 @@ extern "C" int cdf_profile_read(int kernel, float* ms, int cap) {
   return n;
 }
 
+extern "C" int cdf_profile_read_all(int32_t* kernel, float* ms, int cap) {
+  for (int i = 0; i < g_prof_n && i < cap; ++i) {
+    if (hipEventSynchronize(g_prof[i].b) != hipSuccess) CDF_FAIL(CDF_ERR_HIP, "cdf_profile_read_all: event sync failed");
+    float t = 0.0f;
+    if (hipEventElapsedTime(&t, g_prof[i].a, g_prof[i].b) != hipSuccess)
+      CDF_FAIL(CDF_ERR_HIP, "cdf_profile_read_all: elapsed time failed");
+    if (kernel) kernel[i] = g_prof[i].id;
+    if (ms) ms[i] = t;
+  }
+  return g_prof_n;
+}
+
 extern "C" size_t cdf_workspace_bytes(int64_t max_rows, int32_t max_dim, int64_t max_nnz) {
   if (max_rows < 0 || max_dim <= 0 || max_nnz < 0) return 0;
   const size_t steps = filter_workspace_bytes(max_rows) +

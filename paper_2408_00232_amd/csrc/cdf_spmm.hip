@@ -1,16 +1,21 @@
 // CSR aggregation Y = A X over the normalised adjacency (Sec. 3.1) and its transposed
 // counterpart for back-propagation (the same kernel on the CSR of A^T).
 //
-// Work split: the stored entries are cut into chunks of 256 to 1024 consecutive entries and
+// Work split: the stored entries are cut into chunks of 64 to 1024 consecutive entries and
 // each wavefront takes one chunk, whatever rows it covers - a power-law degree
 // distribution (rows of 1 to several 10^5 entries) therefore loads every wavefront
 // equally. Inside a chunk the wavefront walks the entries in storage order: the 64
-// lanes first fetch 64 (column, value) pairs with one coalesced load each, then every
-// entry's feature row is gathered by the whole wavefront (lane l reads elements
-// [l*EPV, l*EPV+EPV) of each 64*EPV-wide pass, a contiguous 16-byte-per-lane read),
-// several gathers in flight at a time, and accumulated in fp32 registers. Column ids
-// and values reach all lanes through v_readlane (scalar broadcast), not LDS. Row ends
-// are wave-uniform: at a row end the accumulator is stored as one coalesced row of Y.
+// lanes first fetch 64 (column, value) pairs with one coalesced load each, then the
+// entries' feature rows are gathered, several gather instructions in flight at a time,
+// and accumulated in fp32 registers. Row ends are wave-uniform: at a row end the
+// accumulator is stored as one coalesced row of Y.
+//
+// Two kernels. spmm_kernel gives the whole wavefront to one entry at a time (lane l reads
+// elements [l*EPV, l*EPV+EPV) of each 64*EPV-wide pass; column ids and values reach all lanes
+// through v_readlane). spmm_sliced_kernel gives LPR lanes to an entry, so one gather
+// instruction serves 64 / LPR entries: rows of whole 128-byte lines are processed in vertical
+// slices of one line (LPR = 8), rows of at most 32 lane-vectors in one slice whose lane group is
+// just wide enough for the row (LPR = 2 ... 32).
 //
 // Rows that straddle chunk borders: the piece at the start of a chunk that continues an
 // earlier row goes to phead[chunk], the piece at the end of a chunk that continues into
@@ -20,7 +25,7 @@
 
 namespace cdf {
 
-constexpr int kChunk = 256;        // stored entries per wavefront (smallest; sizes the workspace)
+constexpr int kChunk = 256;        // stored entries per wavefront on matrices of 1 M entries or more (smallest there)
 constexpr int kSpmmThreads = 256;  // 4 wavefronts per block
 constexpr int kSpmmWaves = kSpmmThreads / 64;
 
@@ -202,7 +207,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
 // and in the memory-side cache; the CSR arrays are re-read once per slice (8 bytes per entry
 // against SW * 4 of features). Entries of a row are spread round-robin over the lane groups and
 // the groups' partial sums are combined when the row ends - a fixed order, no atomics.
-template <typename T, int EPV, int LPR, int U>
+template <typename T, int EPV, int LPR, int UREQ>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_sliced_kernel(
     const int64_t* __restrict__ rowptr, const int* __restrict__ colidx, const float* __restrict__ vals,
     int n_rows, int64_t nnz, const T* __restrict__ X, int64_t ldx, T* __restrict__ Y, T* __restrict__ Y2,
@@ -210,12 +215,14 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_sliced_kernel(
     float* __restrict__ ptail, int* __restrict__ tail_row, int kChunk) {
   constexpr int EPI = 64 / LPR;  // stored entries per gather instruction
   constexpr int SW = LPR * EPV;  // slice width in elements
+  constexpr int U = UREQ * EPI > 64 ? 64 / EPI : UREQ;  // gather instructions in flight (a window holds 64 entries)
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + wave;
   if (chunk >= nchunks) return;
   const int g = lane / LPR, lg = lane % LPR;
   const int col0 = blockIdx.y * SW + lg * EPV;  // this lane's columns: [col0, col0 + EPV)
+  const bool lane_on = col0 < dim;              // false on the lanes past the row end in a partial last slice
   const int64_t s = chunk * kChunk;
   const int L = static_cast<int>(nnz - s < kChunk ? nnz - s : kChunk);
   int my_col = 0, krel = 0;
@@ -295,7 +302,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_sliced_kernel(
     for (int c = 0; c < FIN; ++c) fin[c] = a[c];
   };
   auto store_y = [&](int row, const float (&fin)[FIN]) {
-    if (!owner) return;
+    if (!owner || !lane_on) return;
     const int64_t at = static_cast<int64_t>(row) * ldy + col0 + cbase;
     if (Y) VecIO<T, FIN>::store(Y + at, fin);
     if (Y2) {
@@ -306,7 +313,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_sliced_kernel(
     }
   };
   auto store_partial = [&](float* buf, const float (&fin)[FIN]) {
-    if (!owner) return;
+    if (!owner || !lane_on) return;
     float* pp = buf + chunk * static_cast<int64_t>(dim) + col0 + cbase;
 #pragma unroll
     for (int c = 0; c < FIN; ++c) pp[c] = fin[c];
@@ -340,7 +347,7 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_sliced_kernel(
         v[u] = __shfl(my_val, e, kWave);
 #pragma unroll
         for (int q = 0; q < EPV; ++q) x[u][q] = 0.0f;
-        if (e < cnt) VecIO<T, EPV>::load(xs + static_cast<int64_t>(c) * ldx, x[u]);
+        if (e < cnt && lane_on) VecIO<T, EPV>::load(xs + static_cast<int64_t>(c) * ldx, x[u]);
       }
 #pragma unroll
       for (int u = 0; u < U; ++u) {
@@ -432,72 +439,105 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_fixup_kernel(
   }
 }
 
-int64_t spmm_chunks(int64_t nnz) { return nnz <= 0 ? 1 : ceil_div(nnz, kChunk); }
-
-size_t spmm_workspace_bytes(int64_t nnz, int32_t dim) {
-  const int64_t nc = spmm_chunks(nnz);
-  return align_up(static_cast<size_t>(nc) * 2 * sizeof(int), 256) +
-         2 * align_up(static_cast<size_t>(nc) * dim * sizeof(float), 256);
+// Entries per wavefront: 64 or 128 on small matrices (so that even a few thousand entries spread over
+// all compute units and a wavefront's serial walk stays short), 256 from 1 M entries, up to 1024 for
+// large ones (fewer straddling-row pieces). Always a multiple of 64; a function of nnz alone.
+static int pick_chunk(int64_t nnz) {
+  int c = 64;
+  while (c < kChunk && nnz / (2 * c) >= 4096) c *= 2;
+  while (c >= kChunk && c < 1024 && nnz / (2 * c) >= 65536) c *= 2;
+  return c;
 }
 
-// Entries per wavefront: 256 for small matrices (enough wavefronts to fill 256 CUs), up to 1024
-// for large ones (fewer straddling-row pieces). Always a multiple of 64 and >= kChunk.
-static int pick_chunk(int64_t nnz) {
-  int c = kChunk;
-  while (c < 1024 && nnz / (2 * c) >= 65536) c *= 2;
-  return c;
+int64_t spmm_chunks(int64_t nnz) { return nnz <= 0 ? 1 : ceil_div(nnz, pick_chunk(nnz)); }
+
+// Upper bound of spmm_chunks over every matrix of at most nnz entries (the chunk size steps up with nnz,
+// so the count itself is not monotone).
+static int64_t spmm_chunks_bound(int64_t nnz) {
+  if (nnz <= 0) return 1;
+  const int64_t small = ceil_div(nnz, 64) < 8192 ? ceil_div(nnz, 64) : 8192;
+  const int64_t large = ceil_div(nnz, kChunk);
+  return small > large ? small : large;
+}
+
+size_t spmm_workspace_bytes(int64_t nnz, int32_t dim) {
+  const int64_t nc = spmm_chunks_bound(nnz);
+  return align_up(static_cast<size_t>(nc) * 2 * sizeof(int), 256) +
+         2 * align_up(static_cast<size_t>(nc) * dim * sizeof(float), 256);
 }
 
 template <typename T, int EPV>
 static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, int64_t ldy, int dim, void* ws,
                        hipStream_t st) {
   const int chunk = pick_chunk(A->nnz);
-  const int64_t nc = A->nnz <= 0 ? 1 : ceil_div(A->nnz, chunk);
+  const int64_t nc = spmm_chunks(A->nnz);
   char* w = static_cast<char*>(ws);
-  int* chunk_row = reinterpret_cast<int*>(w);
-  int* tail_row = chunk_row + nc;
+  int* own_chunk_row = reinterpret_cast<int*>(w);
+  int* tail_row = own_chunk_row + nc;
   w += align_up(static_cast<size_t>(nc) * 2 * sizeof(int), 256);
   float* phead = reinterpret_cast<float*>(w);
   w += align_up(static_cast<size_t>(nc) * dim * sizeof(float), 256);
   float* ptail = reinterpret_cast<float*>(w);
 
-  {
-    ProfScope ps(K_SPMM_PLAN, st);
-    chunk_rows_kernel<<<static_cast<unsigned>(ceil_div(A->n_rows, 256)), 256, 0, st>>>(A->rowptr, A->n_rows, chunk_row,
-                                                                                       chunk);
+  // chunk -> row table: the caller's plan (built once per matrix by cdf_spmm_plan), else rebuilt here
+  const int* chunk_row = A->plan;
+  if (!chunk_row) {
+    {
+      ProfScope ps(K_SPMM_PLAN, st);
+      chunk_rows_kernel<<<static_cast<unsigned>(ceil_div(A->n_rows, 256)), 256, 0, st>>>(A->rowptr, A->n_rows,
+                                                                                         own_chunk_row, chunk);
+    }
+    CDF_LAUNCH_CHECK("cdf_spmm/chunk_rows");
+    chunk_row = own_chunk_row;
   }
-  CDF_LAUNCH_CHECK("cdf_spmm/chunk_rows");
   const unsigned nblocks = static_cast<unsigned>(ceil_div(nc, kSpmmWaves));
   const int per_pass = 64 * EPV;
   const int np = static_cast<int>(ceil_div(dim, per_pass));
+  const int nvec = dim / EPV;
+  constexpr bool lane16 = EPV * static_cast<int>(sizeof(T)) == 16;   // 16-byte lane vectors
 #define CDF_SPMM_ARGS                                                                                      \
-  <<<nblocks, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, Y2, ldy, dim, \
-                                     chunk_row, nc, phead, ptail, tail_row, chunk)
-  // rows of 64 * EPV elements or more, in whole slices: the column-sliced kernel
-  // (one 128-byte line per row and slice when the element type allows: 8 lanes of 16 bytes)
-  // It pays when rows hold enough entries to amortise the per-row, per-slice reduction and store.
+  (A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, Y2, ldy, dim, chunk_row, nc, phead, ptail, \
+   tail_row, chunk)
+  // Lanes per entry. Rows of whole 128-byte lines with eight or more entries on average: one line per
+  // row and slice (8 lanes of 16 bytes); it pays when the per-row, per-slice reduction and store are
+  // amortised. Rows of at most 32 lane-vectors: one slice, the lane group just wide enough for the row.
+  // Everything else: the whole wavefront per entry.
   constexpr int min_avg = 8;
-  const int lpr = dim % (8 * EPV) == 0 && A->nnz >= static_cast<int64_t>(min_avg) * A->n_rows ? 8 : 0;
-  if (lpr > 0 && EPV * static_cast<int>(sizeof(T)) == 16) {
-    const dim3 grid(nblocks, static_cast<unsigned>(dim / (lpr * EPV)));
-    prof_begin(K_SPMM_SLICED, st);
-#define CDF_SLICED(UV)                                                                                          \
-  spmm_sliced_kernel<T, EPV, 8, UV><<<grid, kSpmmThreads, 0, st>>>(A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, \
-                                                                   X, ldx, Y, Y2, ldy, dim, chunk_row, nc, phead, \
-                                                                   ptail, tail_row, chunk)
-    // gather instructions in flight per wavefront: long rows (the forward matrix of a power-law
-    // partition averages ~70 entries) run 2-3 % faster with eight, short rows (its transpose, ~20)
-    // with four - measured both ways
-    if (A->nnz >= static_cast<int64_t>(40) * A->n_rows) { CDF_SLICED(8); } else { CDF_SLICED(4); }
-#undef CDF_SLICED
-    prof_end(K_SPMM_SLICED, st);
-    CDF_LAUNCH_CHECK("cdf_spmm/sliced");
+  int lpr = 0, slices = 1;
+  if (lane16 && dim % (8 * EPV) == 0 && A->nnz >= static_cast<int64_t>(min_avg) * A->n_rows) {
+    lpr = 8;
+    slices = dim / (8 * EPV);
+  } else if (lane16 && nvec <= 32) {
+    lpr = 2;
+    while (lpr < nvec) lpr <<= 1;
+  }
+  if (lpr > 0) {
+    if constexpr (lane16) {
+      const dim3 grid(nblocks, static_cast<unsigned>(slices));
+      prof_begin(K_SPMM_SLICED, st);
+      // gather instructions in flight per wavefront: long rows (the forward matrix of a power-law
+      // partition averages ~70 entries) run 2-3 % faster with eight, short rows (its transpose, ~20)
+      // with four - measured both ways
+      const bool deep = A->nnz >= static_cast<int64_t>(40) * A->n_rows;
+      switch (lpr) {
+        case 2: spmm_sliced_kernel<T, EPV, 2, 4><<<grid, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS; break;
+        case 4: spmm_sliced_kernel<T, EPV, 4, 4><<<grid, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS; break;
+        case 8:
+          if (deep) spmm_sliced_kernel<T, EPV, 8, 8><<<grid, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
+          else spmm_sliced_kernel<T, EPV, 8, 4><<<grid, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
+          break;
+        case 16: spmm_sliced_kernel<T, EPV, 16, 4><<<grid, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS; break;
+        default: spmm_sliced_kernel<T, EPV, 32, 4><<<grid, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS; break;
+      }
+      prof_end(K_SPMM_SLICED, st);
+      CDF_LAUNCH_CHECK("cdf_spmm/sliced");
+    }
   } else {
     prof_begin(K_SPMM, st);
-    if (np <= 1) spmm_kernel<T, EPV, 1> CDF_SPMM_ARGS;
-    else if (np <= 2) spmm_kernel<T, EPV, 2> CDF_SPMM_ARGS;
-    else if (np <= 4) spmm_kernel<T, EPV, 4> CDF_SPMM_ARGS;
-    else spmm_kernel<T, EPV, 8> CDF_SPMM_ARGS;
+    if (np <= 1) spmm_kernel<T, EPV, 1><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
+    else if (np <= 2) spmm_kernel<T, EPV, 2><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
+    else if (np <= 4) spmm_kernel<T, EPV, 4><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
+    else spmm_kernel<T, EPV, 8><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
     prof_end(K_SPMM, st);
     CDF_LAUNCH_CHECK("cdf_spmm/main");
   }
@@ -571,4 +611,26 @@ extern "C" int cdf_spmm_fwd(const cdf_csr* A, const void* X, int64_t ldx, void* 
 extern "C" int cdf_spmm_bwd(const cdf_csr* At, const void* dY, int64_t ldy, void* dX, int64_t ldx, int32_t dim,
                             cdf_dtype dt, void* ws, size_t ws_bytes, void* stream) {
   return spmm_run("cdf_spmm_bwd", At, dY, ldy, dX, nullptr, ldx, dim, dt, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+extern "C" size_t cdf_spmm_plan_bytes(int64_t nnz) {
+  return nnz < 0 ? 0 : align_up(static_cast<size_t>(spmm_chunks(nnz)) * sizeof(int), 256);
+}
+
+extern "C" int cdf_spmm_plan(const cdf_csr* A, int32_t* plan, size_t plan_bytes, void* stream) {
+  CDF_REQUIRE(A != nullptr, "cdf_spmm_plan: matrix is null");
+  CDF_REQUIRE(A->n_rows >= 0 && A->nnz >= 0, "cdf_spmm_plan: bad shape rows=%d nnz=%lld", A->n_rows, (long long)A->nnz);
+  if (!plan || !aligned(plan, 4) || plan_bytes < cdf_spmm_plan_bytes(A->nnz))
+    CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_spmm_plan: plan buffer too small (%zu < %zu)", plan_bytes,
+             cdf_spmm_plan_bytes(A->nnz));
+  if (A->n_rows == 0) return CDF_OK;
+  CDF_REQUIRE(A->rowptr && aligned(A->rowptr, 8), "cdf_spmm_plan: row pointers null or misaligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  {
+    ProfScope ps(K_SPMM_PLAN, st);
+    chunk_rows_kernel<<<static_cast<unsigned>(ceil_div(A->n_rows, 256)), 256, 0, st>>>(A->rowptr, A->n_rows, plan,
+                                                                                       pick_chunk(A->nnz));
+  }
+  CDF_LAUNCH_CHECK("cdf_spmm_plan");
+  return CDF_OK;
 }

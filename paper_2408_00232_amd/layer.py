@@ -8,14 +8,19 @@ from . import binding as B
 
 
 class DeviceCsr:
-    """CSR arrays on the device plus the host struct that points at them."""
+    """CSR arrays on the device plus the host struct that points at them (and, by default, the
+    work-split table of the aggregation, built once here)."""
 
-    def __init__(self, n_rows, n_cols, rowptr, colidx, vals, device="cuda:0"):
+    def __init__(self, n_rows, n_cols, rowptr, colidx, vals, device="cuda:0", plan=True):
         self.rowptr = rowptr.to(device=device, dtype=torch.int64).contiguous()
         self.colidx = colidx.to(device=device, dtype=torch.int32).contiguous()
         self.vals = vals.to(device=device, dtype=torch.float32).contiguous()
         self.n_rows, self.n_cols, self.nnz = n_rows, n_cols, int(self.colidx.numel())
         self.struct = B.make_csr(n_rows, n_cols, self.rowptr, self.colidx, self.vals)
+        self.plan = None
+        if plan and self.rowptr.is_cuda:
+            self.plan = torch.zeros(max(B.cdf_spmm_plan_bytes(self.nnz) // 4, 1), dtype=torch.int32, device=device)
+            B.cdf_spmm_plan(self.struct, self.plan)
 
 
 class LayerBuffers:

@@ -229,7 +229,9 @@ def run_spmm(cdf, rowptr, colidx, vals, n_cols, X, bwd=False):
     return Y
 
 
-@pytest.mark.parametrize("dim", [128, 256, 100, 602, 16, 37, 1, 1024, 3000])
+# widths: whole 128-byte lines (column slices), rows of at most 32 lane-vectors (lane groups of 2 ... 32 lanes,
+# exact and partial), odd widths (narrow lanes, whole wavefront per entry), several passes per row
+@pytest.mark.parametrize("dim", [128, 256, 100, 602, 16, 37, 1, 1024, 3000, 4, 8, 12, 20, 28, 36, 64, 96, 120, 160])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_spmm_tiny_partition(cdf, oracle, dim, dtype):
     P = configs.build_partition(configs.TINY)
@@ -287,6 +289,40 @@ def run_spmm_padded(cdf, rowptr, colidx, vals, n_cols, X, ldx, ldy, bwd=False):
     (cdf.cdf_spmm_bwd if bwd else cdf.cdf_spmm_fwd)(A.struct, Xp[:, :dim], Yp[:, :dim], ws)
     torch.cuda.synchronize()
     return Yp[:, :dim], Yp[:, dim:]
+
+
+@pytest.mark.parametrize("nnz_target", [3000, 500_000, 560_000, 1_020_000, 1_100_000])
+@pytest.mark.parametrize("dim", [32, 20])
+def test_spmm_chunk_size_tiers_and_plan(cdf, oracle, nnz_target, dim):
+    """The entries per wavefront step up with the matrix size (64, 128, 256, ...); matrices on both sides of
+    the steps, with and without the work-split table computed ahead (cdf_spmm_plan): same bits either way,
+    same values as the oracle."""
+    rs = np.random.default_rng(nnz_target + dim)
+    n_rows, n_cols = 3000, 5000
+    lens = rs.zipf(1.6, n_rows).astype(np.int64)
+    lens = np.minimum(lens * 20, 4 * n_cols)
+    lens = (lens * (nnz_target / lens.sum())).astype(np.int64)
+    lens[rs.integers(0, n_rows, 50)] = 0
+    rowptr = np.zeros(n_rows + 1, np.int64)
+    rowptr[1:] = np.cumsum(lens)
+    nnz = int(rowptr[-1])
+    colidx = np.concatenate([np.sort(rs.integers(0, n_cols, l)) for l in lens]).astype(np.int32)
+    vals = rs.standard_normal(nnz).astype(np.float32)
+    X = torch.from_numpy(rs.standard_normal((n_cols, dim)).astype(np.float32))
+    t = (torch.from_numpy(rowptr), torch.from_numpy(colidx), torch.from_numpy(vals))
+    ws = ws_for(cdf, n_rows, dim, nnz)
+    dX = X.to(DEV)
+    outs = []
+    for plan in (True, False):
+        A = cdf.DeviceCsr(n_rows, n_cols, *t, DEV, plan=plan)
+        assert (A.struct.plan is not None) == plan
+        Y = torch.full((n_rows, dim), 3.0, device=DEV)
+        cdf.cdf_spmm_fwd(A.struct, dX, Y, ws)
+        torch.cuda.synchronize()
+        outs.append(Y)
+    assert torch.equal(outs[0], outs[1])
+    want = oracle.spmm(rowptr, colidx, vals, n_cols, X.numpy())
+    assert_rows_close(to_np(outs[0]), want, what="Y")
 
 
 # (dim, ldx, ldy): 16-byte vectors kept (pitch a multiple of 4 / 8 elements) on the column-sliced and the
