@@ -18,8 +18,13 @@
  *  - Element type cdf_dtype: fp32, or bf16 storage with fp32 arithmetic.
  *  - Return value: CDF_OK or a negative cdf_status. Invalid arguments are rejected
  *    on the host before anything is launched. cdf_last_error() gives a host string.
- *  - Inputs are assumed finite. Calls sharing a workspace must be ordered on one
- *    stream; distinct workspaces may run concurrently.
+ *  - Inputs are assumed finite. What a NaN does is nevertheless defined: the row maxima and
+ *    minima of the cache test (LINF) and of the quantiser drop NaN elements (IEEE maxNum / minNum),
+ *    so such a row is judged and scaled by its other elements, a NaN element gets code 0, and a row
+ *    that holds only NaN is never sent; with CDF_NORM_L2 a NaN makes both sums NaN and the row is
+ *    not sent (comparisons with NaN are false).
+ *  - Calls sharing a workspace must be ordered on one stream; distinct workspaces may run
+ *    concurrently.
  *  - n_rows == 0, max_sent == 0 and *n_sent == 0 are valid and do nothing.
  */
 #ifndef CDF_H
@@ -150,7 +155,16 @@ int cdf_cache_filter_static(const void* cur, const void* cached, int32_t n_rows,
  *   NONE leaves the cache.
  * cached may be NULL only if delta == 0 and commit == CDF_COMMIT_NONE.
  * max_sent bounds *n_sent (capacity of idx / codes / meta); bits is 8 or 4.
+ * Width limit (cdf_quantize, cdf_dequantize, cdf_cache_filter_quantize and the layer steps, which
+ * call them): a row is held in registers, 512 lane-vectors at most, so dim <= 512 * v where v is the
+ * number of elements per lane-vector: 4 if dim and ld are multiples of 4 and every row pointer is
+ * aligned to 4 elements, else 2 under the same conditions for 2, else 1 - dim <= 2048, 1024 or 512.
+ * Wider rows are refused with CDF_ERR_UNSUPPORTED before anything is launched; cdf_max_message_dim
+ * gives the limit for a width, pitch and type (base pointers taken as aligned). cdf_cache_filter and
+ * the aggregation have no such limit.
  */
+int32_t cdf_max_message_dim(int32_t dim, int64_t ld, cdf_dtype dt);
+
 int cdf_quantize(const void* cur, void* cached, const int32_t* idx, const int32_t* n_sent,
                  int32_t max_sent, int32_t dim, int64_t ld, cdf_dtype dt, int bits, cdf_qscheme qs,
                  cdf_commit commit, int delta, uint8_t* codes, float* meta, void* stream);

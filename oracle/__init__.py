@@ -13,7 +13,10 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "cdf_oracle.c")
-_LIB = os.path.join(_HERE, "libcdf_oracle.so")
+# CDF_ORACLE_SANITIZE=1 selects a second build of the same source with AddressSanitizer and
+# UndefinedBehaviorSanitizer (the process must then have gcc's libasan preloaded)
+_SANITIZE = os.environ.get("CDF_ORACLE_SANITIZE", "") not in ("", "0")
+_LIB = os.path.join(_HERE, "libcdf_oracle_san.so" if _SANITIZE else "libcdf_oracle.so")
 
 F32, BF16 = 0, 1
 NORM_LINF, NORM_L2 = 0, 1
@@ -28,6 +31,8 @@ def build(force: bool = False) -> str:
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-shared",
                "-fPIC", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        if _SANITIZE:
+            cmd[1:2] = ["-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"]
         subprocess.check_call(cmd)
     return _LIB
 

@@ -11,7 +11,10 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libcdf.so")
+# CDF_LIB_SANITIZE=1 selects the build whose host code carries AddressSanitizer / UBSan instrumentation
+# (paper_2408_00232_amd.build.build_lib(sanitize_host=True)); used by the CPU test suite only
+LIB_PATH = os.path.join(_HERE, "libcdf_san.so" if os.environ.get("CDF_LIB_SANITIZE", "") not in ("", "0")
+                        else "libcdf.so")
 
 F32, BF16 = 0, 1
 NORM_LINF, NORM_L2 = 0, 1
@@ -20,7 +23,7 @@ COMMIT_NONE, COMMIT_CUR, COMMIT_DEQ = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf_profile_kernel_name", "cdf_profile_read", "cdf_profile_read_all",
-           "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_cache_filter", "cdf_cache_filter_static", "cdf_quantize", "cdf_cache_filter_quantize",
+           "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_max_message_dim", "cdf_cache_filter", "cdf_cache_filter_static", "cdf_quantize", "cdf_cache_filter_quantize",
            "cdf_dequantize", "cdf_spmm_plan_bytes", "cdf_spmm_plan", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
            "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd",
            "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_gather_rows", "cdf_map_index",
@@ -212,6 +215,10 @@ def cdf_workspace_bytes(max_rows: int, max_dim: int, max_nnz: int) -> int:
 
 def cdf_code_row_bytes(dim: int, bits: int, qs: int) -> int:
     return int(load().cdf_code_row_bytes(dim, bits, qs))
+
+
+def cdf_max_message_dim(dim: int, ld: int, dt: int) -> int:
+    return int(load().cdf_max_message_dim(ctypes.c_int32(dim), ctypes.c_int64(ld), ctypes.c_int(dt)))
 
 
 def cdf_cache_filter(cur, cached, eps, norm, mask, idx, n_sent, ws):

@@ -26,17 +26,27 @@ def sources_sha() -> str:
     return h.hexdigest()[:16]
 
 
-def build_lib(verbose: bool = True) -> str:
-    """Compile every source to an object (in parallel), then link the shared library."""
+LIB_SANITIZED = os.path.join(HERE, "libcdf_san.so")
+SANITIZE_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                  "-Xarch_host", "-fno-sanitize-recover=undefined", "-g"]
+
+
+def build_lib(verbose: bool = True, sanitize_host: bool = False) -> str:
+    """Compile every source to an object (in parallel), then link the shared library.
+    sanitize_host: a second library, libcdf_san.so, whose HOST code (argument checks, launch logic, the
+    partitioner) is instrumented with AddressSanitizer and UndefinedBehaviorSanitizer; device code is
+    unchanged. A process that loads it needs clang's ASan runtime preloaded (asan_runtime())."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    bdir = os.path.join(HERE, "_build")
+    bdir = os.path.join(HERE, "_build", "san" if sanitize_host else "")
+    lib_path = LIB_SANITIZED if sanitize_host else LIB
+    flags = FLAGS + (SANITIZE_FLAGS if sanitize_host else [])
     os.makedirs(bdir, exist_ok=True)
     procs = []
     objs = []
     for s in SOURCES:
         obj = os.path.join(bdir, s.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [hipcc, "-c", os.path.join(CSRC, s), "-o", obj] + FLAGS
+        cmd = [hipcc, "-c", os.path.join(CSRC, s), "-o", obj] + flags
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -51,9 +61,19 @@ def build_lib(verbose: bool = True) -> str:
             print(f"hipcc failed on {s}", file=sys.stderr)
     if failed:
         raise RuntimeError("libcdf build failed")
-    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
+    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", lib_path] + objs
+    if sanitize_host:
+        cmd += ["-fsanitize=address", "-fsanitize=undefined", "-shared-libsan", "-fno-gpu-sanitize"]
     subprocess.check_call(cmd)
-    return LIB
+    return lib_path
+
+
+def asan_runtime() -> str:
+    """Path of the ASan runtime of the compiler hipcc drives (to be preloaded by a process that loads
+    libcdf_san.so)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = subprocess.check_output([hipcc, "-print-file-name=libclang_rt.asan-x86_64.so"], text=True).strip()
+    return out
 
 
 if __name__ == "__main__":

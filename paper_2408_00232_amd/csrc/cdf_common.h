@@ -99,23 +99,8 @@ typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 template <typename T, int EPV>
 struct VecIO;
 
-// Streaming variants: the non-temporal hint asks the caches not to keep the line.
-template <typename V>
-__device__ __forceinline__ V nt_load(const V* p) { return __builtin_nontemporal_load(p); }
-template <typename V>
-__device__ __forceinline__ void nt_store(V* p, V v) { __builtin_nontemporal_store(v, p); }
-
 template <>
 struct VecIO<float, 4> {
-  static __device__ __forceinline__ void load_nt(const float* p, float (&v)[4]) {
-    f32x4_t t = nt_load(reinterpret_cast<const f32x4_t*>(p));
-    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-  }
-  static __device__ __forceinline__ void store_nt(float* p, const float (&v)[4]) {
-    f32x4_t t;
-    t.x = v[0]; t.y = v[1]; t.z = v[2]; t.w = v[3];
-    nt_store(reinterpret_cast<f32x4_t*>(p), t);
-  }
   static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
     float4 t = *reinterpret_cast<const float4*>(p);
     v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
@@ -126,15 +111,6 @@ struct VecIO<float, 4> {
 };
 template <>
 struct VecIO<float, 2> {
-  static __device__ __forceinline__ void load_nt(const float* p, float (&v)[2]) {
-    f32x2_t t = nt_load(reinterpret_cast<const f32x2_t*>(p));
-    v[0] = t.x; v[1] = t.y;
-  }
-  static __device__ __forceinline__ void store_nt(float* p, const float (&v)[2]) {
-    f32x2_t t;
-    t.x = v[0]; t.y = v[1];
-    nt_store(reinterpret_cast<f32x2_t*>(p), t);
-  }
   static __device__ __forceinline__ void load(const float* p, float (&v)[2]) {
     float2 t = *reinterpret_cast<const float2*>(p);
     v[0] = t.x; v[1] = t.y;
@@ -145,29 +121,11 @@ struct VecIO<float, 2> {
 };
 template <>
 struct VecIO<float, 1> {
-  static __device__ __forceinline__ void load_nt(const float* p, float (&v)[1]) {
-    float t = nt_load(reinterpret_cast<const float*>(p));
-    v[0] = t;
-  }
-  static __device__ __forceinline__ void store_nt(float* p, const float (&v)[1]) {
-    float t;
-    t = v[0];
-    nt_store(reinterpret_cast<float*>(p), t);
-  }
   static __device__ __forceinline__ void load(const float* p, float (&v)[1]) { v[0] = *p; }
   static __device__ __forceinline__ void store(float* p, const float (&v)[1]) { *p = v[0]; }
 };
 template <>
 struct VecIO<bf16_t, 8> {
-  static __device__ __forceinline__ void load_nt(const bf16_t* p, float (&v)[8]) {
-    u32x4_t t = nt_load(reinterpret_cast<const u32x4_t*>(p));
-    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u); v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u); v[4] = __uint_as_float(t.z << 16); v[5] = __uint_as_float(t.z & 0xffff0000u); v[6] = __uint_as_float(t.w << 16); v[7] = __uint_as_float(t.w & 0xffff0000u);
-  }
-  static __device__ __forceinline__ void store_nt(bf16_t* p, const float (&v)[8]) {
-    u32x4_t t;
-    t.x = f2bf(v[0]) | (static_cast<uint32_t>(f2bf(v[1])) << 16); t.y = f2bf(v[2]) | (static_cast<uint32_t>(f2bf(v[3])) << 16); t.z = f2bf(v[4]) | (static_cast<uint32_t>(f2bf(v[5])) << 16); t.w = f2bf(v[6]) | (static_cast<uint32_t>(f2bf(v[7])) << 16);
-    nt_store(reinterpret_cast<u32x4_t*>(p), t);
-  }
   static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
     uint4 t = *reinterpret_cast<const uint4*>(p);
     v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
@@ -186,15 +144,6 @@ struct VecIO<bf16_t, 8> {
 };
 template <>
 struct VecIO<bf16_t, 4> {
-  static __device__ __forceinline__ void load_nt(const bf16_t* p, float (&v)[4]) {
-    u32x2_t t = nt_load(reinterpret_cast<const u32x2_t*>(p));
-    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u); v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
-  }
-  static __device__ __forceinline__ void store_nt(bf16_t* p, const float (&v)[4]) {
-    u32x2_t t;
-    t.x = f2bf(v[0]) | (static_cast<uint32_t>(f2bf(v[1])) << 16); t.y = f2bf(v[2]) | (static_cast<uint32_t>(f2bf(v[3])) << 16);
-    nt_store(reinterpret_cast<u32x2_t*>(p), t);
-  }
   static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[4]) {
     uint2 t = *reinterpret_cast<const uint2*>(p);
     v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
@@ -209,15 +158,6 @@ struct VecIO<bf16_t, 4> {
 };
 template <>
 struct VecIO<bf16_t, 2> {
-  static __device__ __forceinline__ void load_nt(const bf16_t* p, float (&v)[2]) {
-    uint32_t t = nt_load(reinterpret_cast<const uint32_t*>(p));
-    v[0] = __uint_as_float(t << 16); v[1] = __uint_as_float(t & 0xffff0000u);
-  }
-  static __device__ __forceinline__ void store_nt(bf16_t* p, const float (&v)[2]) {
-    uint32_t t;
-    t = f2bf(v[0]) | (static_cast<uint32_t>(f2bf(v[1])) << 16);
-    nt_store(reinterpret_cast<uint32_t*>(p), t);
-  }
   static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[2]) {
     uint32_t t = *reinterpret_cast<const uint32_t*>(p);
     v[0] = __uint_as_float(t << 16); v[1] = __uint_as_float(t & 0xffff0000u);
@@ -228,15 +168,6 @@ struct VecIO<bf16_t, 2> {
 };
 template <>
 struct VecIO<bf16_t, 1> {
-  static __device__ __forceinline__ void load_nt(const bf16_t* p, float (&v)[1]) {
-    uint16_t t = nt_load(reinterpret_cast<const uint16_t*>(p));
-    v[0] = bf2f(t);
-  }
-  static __device__ __forceinline__ void store_nt(bf16_t* p, const float (&v)[1]) {
-    uint16_t t;
-    t = f2bf(v[0]);
-    nt_store(reinterpret_cast<uint16_t*>(p), t);
-  }
   static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[1]) { v[0] = bf2f(*p); }
   static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[1]) { *p = f2bf(v[0]); }
 };

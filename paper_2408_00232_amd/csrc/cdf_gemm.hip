@@ -293,8 +293,9 @@ static void dw_split(int n, int f, int g, int* slab_rows, int* slabs) {
   const size_t per = static_cast<size_t>(f) * g * sizeof(float);
   // enough blocks to fill the chip a few times over (tiles x slabs >= ~1500), not more
   const int64_t tiles = ceil_div(f, kBM) * ceil_div(g, g > 64 ? 128 : 64);
-  while (ceil_div(n, rows * 2) * tiles >= 1536) rows *= 2;
-  while (static_cast<size_t>(ceil_div(n, rows)) * per > kDwPartialCap) rows *= 2;
+  // (both loops stop at one slab at the latest: rows >= n)
+  while (rows < n && ceil_div(n, rows * 2) * tiles >= 1536) rows *= 2;
+  while (rows < n && static_cast<size_t>(ceil_div(n, rows)) * per > kDwPartialCap) rows *= 2;
   *slab_rows = static_cast<int>(rows);
   *slabs = static_cast<int>(ceil_div(n > 0 ? n : 1, rows));
 }

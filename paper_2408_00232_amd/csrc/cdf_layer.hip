@@ -162,6 +162,9 @@ extern "C" int cdf_gcn_layer_fwd(const cdf_layer_fwd_args* p, void* ws, size_t w
               p->n_loc + p->n_halo);
   CDF_REQUIRE(p->xfull && p->W && p->M && p->H, "cdf_gcn_layer_fwd: null matrix");
   if (p->dt != CDF_F32 && p->dt != CDF_BF16) CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_gcn_layer_fwd: dtype %d", (int)p->dt);
+  if (p->n_halo > 0 && p->f_in > cdf_max_message_dim(p->f_in, p->f_in, p->dt))
+    CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_gcn_layer_fwd: halo rows of %d elements are wider than the message kernels take (%d)",
+             p->f_in, cdf_max_message_dim(p->f_in, p->f_in, p->dt));
   const size_t fw = filter_workspace_bytes(p->n_halo);
   const size_t need = fw + spmm_workspace_bytes(p->A->nnz, p->f_in);
   if (!ws || !aligned(ws, 256) || ws_bytes < need)
@@ -196,6 +199,9 @@ extern "C" int cdf_gcn_layer_bwd(const cdf_layer_bwd_args* p, void* ws, size_t w
                 "cdf_gcn_layer_bwd: transposed adjacency is %d x %d, expected %d x %d", p->At->n_rows, p->At->n_cols,
                 p->n_loc + p->n_halo, p->n_loc);
   }
+  if (p->need_dx && p->n_halo > 0 && p->f_in > cdf_max_message_dim(p->f_in, p->f_in, p->dt))
+    CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_gcn_layer_bwd: halo rows of %d elements are wider than the message kernels take (%d)",
+             p->f_in, cdf_max_message_dim(p->f_in, p->f_in, p->dt));
   const size_t fw = filter_workspace_bytes(p->n_halo);
   size_t need = fw + dense_workspace_bytes(p->n_loc, p->f_in, p->f_out);
   if (p->need_dx) need = max_sz(need, fw + spmm_workspace_bytes(p->At->nnz, p->f_in));
@@ -226,6 +232,9 @@ extern "C" int cdf_gcn_layer_tf_fwd(const cdf_layer_tf_fwd_args* p, void* ws, si
               "cdf_gcn_layer_tf_fwd: adjacency is %d x %d, expected %d x %d", p->A->n_rows, p->A->n_cols, p->n_loc,
               p->n_loc + p->n_halo);
   CDF_REQUIRE(p->x_local && p->W && p->tfull && p->H, "cdf_gcn_layer_tf_fwd: null matrix");
+  if (p->n_halo > 0 && p->f_out > cdf_max_message_dim(p->f_out, p->f_out, CDF_F32))
+    CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_gcn_layer_tf_fwd: halo rows of %d elements are wider than the message kernels take (%d)",
+             p->f_out, cdf_max_message_dim(p->f_out, p->f_out, CDF_F32));
   const size_t fw = filter_workspace_bytes(p->n_halo);
   const size_t need = fw + spmm_workspace_bytes(p->A->nnz, p->f_out);
   if (!ws || !aligned(ws, 256) || ws_bytes < need)
@@ -266,6 +275,9 @@ extern "C" int cdf_gcn_layer_tf_bwd(const cdf_layer_tf_bwd_args* p, void* ws, si
               p->n_loc + p->n_halo, p->n_loc);
   CDF_REQUIRE(p->dH && p->x_local && p->W && p->dtfull && p->dW && (!p->relu || (p->Zs && p->dZ)),
               "cdf_gcn_layer_tf_bwd: null matrix");
+  if (p->n_halo > 0 && p->f_out > cdf_max_message_dim(p->f_out, p->f_out, CDF_F32))
+    CDF_FAIL(CDF_ERR_UNSUPPORTED, "cdf_gcn_layer_tf_bwd: halo rows of %d elements are wider than the message kernels take (%d)",
+             p->f_out, cdf_max_message_dim(p->f_out, p->f_out, CDF_F32));
   const size_t fw = filter_workspace_bytes(p->n_halo);
   size_t need = fw + spmm_workspace_bytes(p->At->nnz, p->f_out);
   need = max_sz(need, fw + dense_workspace_bytes(p->n_loc, p->f_in, p->f_out));

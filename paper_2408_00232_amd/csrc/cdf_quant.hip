@@ -434,6 +434,13 @@ extern "C" size_t cdf_code_row_bytes(int32_t dim, int bits, cdf_qscheme qs) {
   return (static_cast<size_t>(dim) * bits + 7) / 8;
 }
 
+// Widest row the message kernels take for this width / pitch / type, assuming 16-byte aligned base
+// pointers: 512 lane-vectors of the widest vector both allow.
+extern "C" int32_t cdf_max_message_dim(int32_t dim, int64_t ld, cdf_dtype dt) {
+  if (dim <= 0 || ld < dim || (dt != CDF_F32 && dt != CDF_BF16)) return 0;
+  return 512 * pick_epv(dim, ld, elem_bytes(dt), nullptr);
+}
+
 static int check_scheme(const char* fn, int bits, cdf_qscheme qs, cdf_dtype dt) {
   if (dt != CDF_F32 && dt != CDF_BF16) CDF_FAIL(CDF_ERR_UNSUPPORTED, "%s: dtype %d", fn, (int)dt);
   if (qs != CDF_Q_MINMAX && qs != CDF_Q_SYMMETRIC && qs != CDF_Q_NONE)

@@ -143,6 +143,39 @@ def test_cache_filter_edges(cdf, oracle):
         assert int(n_sent.item()) == 0 and int(mask.sum().item()) == 0
 
 
+def test_nan_rows_follow_the_stated_rule(cdf, oracle):
+    """Non-finite input: the kernels take the decisions the header states and the oracle pins (maxima drop
+    NaN elements, L2 sums turn NaN and the row stays), in the separate calls and in the one-pass call."""
+    from test_oracle_pins import nan_rows
+    cur, cached = nan_rows()
+    reps = 40                                   # several blocks of rows
+    cur, cached = np.tile(cur, (reps, 1)), np.tile(cached, (reps, 1))
+    R, F = cur.shape
+    dcur, dcached = torch.from_numpy(cur).to(DEV), torch.from_numpy(cached).to(DEV)
+    mask = torch.zeros(R, dtype=torch.uint8, device=DEV)
+    idx = torch.zeros(R, dtype=torch.int32, device=DEV)
+    n_sent = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ws = ws_for(cdf, R, F)
+    for norm in (0, 1):
+        cdf.cdf_cache_filter(dcur, dcached, 0.05, norm, mask, idx, n_sent, ws)
+        torch.cuda.synchronize()
+        omask, oidx = oracle.cache_filter(cur, cached, 0.05, norm)
+        np.testing.assert_array_equal(to_np(mask), omask)
+        assert int(n_sent.item()) == oidx.size
+    omask, oidx = oracle.cache_filter(cur, cached, 0.05, 0)
+    assert oidx.size == 2 * reps
+    ocodes, ometa = oracle.quantize(cur, cached.copy(), oidx, 8, 0, 0, True)
+    codes = torch.zeros(R * F, dtype=torch.uint8, device=DEV)
+    meta = torch.zeros(R, 2, device=DEV)
+    cdf.cdf_cache_filter_quantize(dcur, dcached, 0.05, 0, 8, 0, 0, True, mask, idx, n_sent, codes, meta, ws)
+    torch.cuda.synchronize()
+    n = int(n_sent.item())
+    assert n == oidx.size
+    np.testing.assert_array_equal(to_np(idx)[:n], oidx)
+    np.testing.assert_array_equal(to_np(codes)[:n * F].reshape(n, F), ocodes)
+    np.testing.assert_array_equal(to_np(meta)[:n], ometa)
+
+
 def test_argument_errors(cdf):
     ws = ws_for(cdf, 64, 64)
     cur = torch.randn(8, 16, device=DEV)

@@ -128,3 +128,45 @@ def test_partition_structs_match_header_layout():
                 if names:
                     fields.append(names[-1])
         assert fields == [f[0] for f in cls._fields_], name
+
+
+def test_message_width_limit_is_stated_and_checked_on_the_host(lib):
+    """Rows wider than 512 lane-vectors are refused before any launch, by the message calls and by the
+    layer steps alike; the limit follows the alignment of width and pitch."""
+    from paper_2408_00232_amd import binding as B
+    assert B.cdf_max_message_dim(2048, 2048, B.F32) == 2048 and B.cdf_max_message_dim(1024, 1024, B.BF16) == 2048
+    assert B.cdf_max_message_dim(602, 602, B.F32) == 1024 and B.cdf_max_message_dim(700, 701, B.F32) == 512
+    fake = ctypes.c_void_p(0x1000)            # never dereferenced: the call is refused on the host
+    c32, c64 = ctypes.c_int32, ctypes.c_int64
+    rc = lib.cdf_quantize(fake, fake, fake, fake, c32(4), c32(2052), c64(2052), 0, 8, 0, 1, 1, fake, fake, None)
+    assert rc == B.ERR_UNSUPPORTED and b"too wide" in lib.cdf_last_error()
+    rc = lib.cdf_dequantize(fake, fake, fake, fake, c32(4), c32(1026), 8, 0, fake, c64(1026), 0, 1, None)
+    assert rc == B.ERR_UNSUPPORTED
+    csr = B.cdf_csr(8, 16, 0, 0x1000, 0x1000, 0x1000, None)
+    args = B.cdf_layer_fwd_args(ctypes.pointer(csr), 8, 8, 4096, 16, B.F32, 1, 0x1000, 0x1000, 0x1000, 0x1000, 0.05, 0, 8,
+                                0, 1, 1, 0x1000, None, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0x1000)
+    rc = lib.cdf_gcn_layer_fwd(ctypes.byref(args), None, ctypes.c_size_t(0), None)
+    assert rc == B.ERR_UNSUPPORTED and b"wider than the message kernels" in lib.cdf_last_error()
+
+
+@pytest.mark.timeout(60)
+def test_dense_bwd_slab_split_terminates_for_large_weight_matrices(lib):
+    """f_in * f_out of 25 M and more: the split of the rows into slabs must still terminate (the call then
+    reports the missing workspace; nothing is launched)."""
+    from paper_2408_00232_amd import binding as B
+    fake = ctypes.c_void_p(0x1000)
+    c32, c64 = ctypes.c_int32, ctypes.c_int64
+    for n in (1, 1000, 3_000_000):
+        rc = lib.cdf_dense_bwd(fake, c64(6144), 0, fake, fake, fake, c32(n), c32(6144), c32(4096), 1, fake, fake, c64(6144),
+                               None, ctypes.c_size_t(0), None)
+        assert rc == B.ERR_WORKSPACE
+
+
+def test_spmm_plan_host_checks(lib):
+    from paper_2408_00232_amd import binding as B
+    assert B.cdf_spmm_plan_bytes(0) == 256 and B.cdf_spmm_plan_bytes(8182) == 512          # 128 chunks of 64 entries
+    chunks = (144_515_404 + 1023) // 1024                                                  # 1024 entries per wavefront
+    assert B.cdf_spmm_plan_bytes(144_515_404) == (chunks * 4 + 255) // 256 * 256
+    csr = B.cdf_csr(8, 16, 100, 0x1000, 0x1000, 0x1000, None)
+    assert lib.cdf_spmm_plan(ctypes.byref(csr), ctypes.c_void_p(0x1000), ctypes.c_size_t(4), None) == B.ERR_WORKSPACE
+    assert lib.cdf_spmm_plan(None, None, ctypes.c_size_t(0), None) == B.ERR_INVALID_ARG

@@ -234,6 +234,35 @@ def test_l2_summation_order_is_the_stated_one(oracle):
         assert m[0] == sent
 
 
+def nan_rows():
+    """Rows with NaN elements, hand-built: what the row maxima must make of them."""
+    nan = np.float32(np.nan)
+    cached = np.array([[1, 2, 4, -3], [1, 2, 4, -3], [1, 2, 4, -3], [0, 0, 0, 0], [1, nan, 4, -3]], np.float32)
+    cur = cached.copy()
+    cur[0] = [1, nan, 4, -3]          # only change is a NaN: the finite elements are unchanged -> not sent
+    cur[1] = [1.5, nan, 4, -3]        # finite change 0.5 > 0.05 * 4 -> sent
+    cur[2] = [nan, nan, nan, nan]     # nothing finite -> difference maximum stays 0 -> not sent
+    cur[3] = [nan, 0, 0, 1e-3]        # zero cache: the finite difference decides -> sent
+    cur[4] = [1, 2, 4, -3]            # NaN in the cache: dropped from both maxima, the rest is unchanged -> not sent
+    return cur, cached
+
+
+def test_nan_elements_are_dropped_by_the_row_maxima(oracle):
+    """The stated behaviour for non-finite input (IEEE maxNum / minNum drop a NaN operand): LINF judges a
+    row by its other elements; L2 sums become NaN and the row is not sent; the quantiser scales by the
+    finite elements and gives a NaN element code 0."""
+    cur, cached = nan_rows()
+    mask, idx = oracle.cache_filter(cur, cached, 0.05, oracle.NORM_LINF)
+    assert mask.tolist() == [0, 1, 0, 1, 0] and idx.tolist() == [1, 3]
+    mask2, _ = oracle.cache_filter(cur, cached, 0.05, oracle.NORM_L2)
+    assert mask2.tolist() == [0, 0, 0, 0, 0]
+    codes, meta = oracle.quantize(cur, cached.copy(), idx, 8, oracle.Q_MINMAX, oracle.COMMIT_NONE, True)
+    # row 1: m = (0.5, NaN, 0, 0) -> lo 0, hi 0.5; codes 255, 0 (NaN), 0, 0
+    assert meta[0].tolist() == [0.0, 0.5] and codes[0].tolist() == [255, 0, 0, 0]
+    # row 3: m = (NaN, 0, 0, 1e-3) -> lo 0, hi 1e-3; codes 0 (NaN), 0, 0, 255
+    assert codes[1].tolist() == [0, 0, 0, 255] and meta[1, 0] == 0.0 and meta[1, 1] == np.float32(1e-3)
+
+
 def test_staleness_bound_after_commits(oracle):
     """After test + commit, every row obeys ||cur - cached|| <= eps ||cached|| (premise of Lemma 2)."""
     rs = np.random.default_rng(8)
