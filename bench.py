@@ -22,7 +22,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
-AGG_KERNELS = ("spmm_kernel", "spmm_sliced_kernel")
+AGG_KERNELS = ("spmm_kernel", "spmm_sliced_kernel", "spmm_kernel<transform>")
 
 
 def log(*a):

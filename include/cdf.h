@@ -226,6 +226,23 @@ int cdf_spmm_bwd(const cdf_csr* At, const void* dY, int64_t ldy, void* dX, int64
                  cdf_dtype dt, void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Aggregation and dense transform of a layer in one call (Sec. 3.1, first equation:
+ * H' = sigma(A^ H W)):  M = A X,  Z = M W,  H = sigma(Z).
+ * When the output is narrow (f_out <= 64), the rows are fp32 with 16-byte aligned pitch and W plus
+ * four row buffers fit 64 KB of LDS, the transform runs in the row epilogue of the aggregation kernel:
+ * a finished row of M is stored (the backward step needs it) and multiplied with W from LDS straight
+ * away, so M is not read back and the dense kernel is not launched. Otherwise the call is
+ * cdf_spmm_fwd followed by cdf_dense_fwd. Same results within fp32 rounding either way; each route is
+ * bit-reproducible. The layer steps keep the two launches: the one-kernel route has to give a whole
+ * wavefront to every stored entry and measured slower on every benchmark workload (the column-sliced
+ * aggregation plus the matrix-core kernel wins even where a step is launch-bound). M [n_rows x f_in] type dt with pitch ldm, Z (nullable) and H (nullable) [n_rows x
+ * f_out] fp32 contiguous; ws as for cdf_spmm_fwd.
+ */
+int cdf_spmm_dense_fwd(const cdf_csr* A /* host */, const void* X, int64_t ldx, cdf_dtype dt, const float* W,
+                       int32_t f_in, int32_t f_out, int relu, void* M, int64_t ldm, float* Z, float* H, void* ws,
+                       size_t ws_bytes, void* stream);
+
+/*
  * Dense transform (Sec. 3.1: Z = (A^ H) W, H' = sigma(Z), sigma = ReLU or identity) on
  * the matrix cores. M [n x f_in] type dt, W [f_in x f_out] fp32 row-major,
  * Z (nullable), H (nullable) [n x f_out] fp32 row-major, contiguous.

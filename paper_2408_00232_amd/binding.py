@@ -24,7 +24,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf_profile_kernel_name", "cdf_profile_read", "cdf_profile_read_all",
            "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_max_message_dim", "cdf_cache_filter", "cdf_cache_filter_static", "cdf_quantize", "cdf_cache_filter_quantize",
-           "cdf_dequantize", "cdf_spmm_plan_bytes", "cdf_spmm_plan", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_dense_fwd", "cdf_dense_bwd",
+           "cdf_dequantize", "cdf_spmm_plan_bytes", "cdf_spmm_plan", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_spmm_dense_fwd", "cdf_dense_fwd", "cdf_dense_bwd",
            "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd",
            "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_gather_rows", "cdf_map_index",
            "cdf_mark_rows", "cdf_active_rows", "cdf_relu_fwd",
@@ -276,6 +276,14 @@ def cdf_spmm_fwd(A: cdf_csr, X, Y, ws):
 
 def cdf_spmm_bwd(At: cdf_csr, dY, dX, ws):
     _spmm("cdf_spmm_bwd", At, dY, dX, ws)
+
+
+def cdf_spmm_dense_fwd(A: cdf_csr, X, W, relu, M, Z, H, ws):
+    rc = load().cdf_spmm_dense_fwd(ctypes.byref(A), _ptr(X), ctypes.c_int64(_ld(X)), ctypes.c_int(dtype_of(X)), _ptr(W),
+                                   ctypes.c_int32(W.shape[0]), ctypes.c_int32(W.shape[1]), ctypes.c_int(1 if relu else 0),
+                                   _ptr(M), ctypes.c_int64(_ld(M)), _ptr(Z), _ptr(H), _ptr(ws),
+                                   ctypes.c_size_t(ws.numel() * ws.element_size()), _stream())
+    _check("cdf_spmm_dense_fwd", rc)
 
 
 def cdf_dense_fwd(M, W, relu, Z, H):

@@ -34,7 +34,7 @@ void set_error(const char* fmt, ...);
 // ---- optional per-kernel timing (host side, HIP events on the launch stream) ----
 enum KernelId {
   K_FILTER = 0, K_SCAN, K_COMPACT, K_QUANTIZE, K_DEQUANTIZE, K_SPMM_PLAN, K_SPMM, K_SPMM_FIXUP,
-  K_GEMM_FWD, K_GEMM_DW, K_GEMM_DW_REDUCE, K_GEMM_DM, K_SPMM_SLICED, K_RELU_MASK, K_TEST_ENCODE, K_GATHER_CODES,
+  K_GEMM_FWD, K_GEMM_DW, K_GEMM_DW_REDUCE, K_GEMM_DM, K_SPMM_SLICED, K_RELU_MASK, K_TEST_ENCODE, K_GATHER_CODES, K_SPMM_XFORM,
   K_COUNT
 };
 void prof_begin(int id, hipStream_t st);

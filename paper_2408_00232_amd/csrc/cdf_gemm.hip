@@ -288,8 +288,10 @@ __global__ __launch_bounds__(256) void reduce_slabs_kernel(const float* __restri
 
 constexpr size_t kDwPartialCap = size_t(512) << 20;  // bytes of slab partials at most
 
+constexpr int kDwMinSlab = 256;  // rows per slab at least (a multiple of the k-tile)
+
 static void dw_split(int n, int f, int g, int* slab_rows, int* slabs) {
-  int64_t rows = 2048;
+  int64_t rows = kDwMinSlab;
   const size_t per = static_cast<size_t>(f) * g * sizeof(float);
   // enough blocks to fill the chip a few times over (tiles x slabs >= ~1500), not more
   const int64_t tiles = ceil_div(f, kBM) * ceil_div(g, g > 64 ? 128 : 64);
@@ -302,11 +304,11 @@ static void dw_split(int n, int f, int g, int* slab_rows, int* slabs) {
 
 // Upper bound of the slab partials for any n' <= n, f' <= f, g' <= g (so that a workspace sized
 // for the largest layer serves every layer): the split keeps slabs * tiles below about 3072 and
-// a tile's partial is at most 128 x 256 floats; never more than one slab per 2048 rows.
+// a tile's partial is at most 128 x 256 floats; never more than one slab per kDwMinSlab rows.
 size_t dense_workspace_bytes(int64_t n, int32_t f, int32_t g) {
   const size_t tiles = static_cast<size_t>(ceil_div(f, kBM)) * static_cast<size_t>(ceil_div(g, 64));
   const size_t by_grid = (3072 + tiles) * static_cast<size_t>(kBM) * 256 * sizeof(float);
-  const size_t by_rows = static_cast<size_t>(ceil_div(n > 0 ? n : 1, 2048)) * f * g * sizeof(float);
+  const size_t by_rows = static_cast<size_t>(ceil_div(n > 0 ? n : 1, kDwMinSlab)) * f * g * sizeof(float);
   return align_up(by_grid < by_rows ? by_grid : by_rows, 256);
 }
 

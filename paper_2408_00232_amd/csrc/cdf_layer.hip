@@ -50,7 +50,7 @@ static const char* const kKernelNames[K_COUNT] = {
     "filter_kernel", "scan_kernel", "compact_kernel", "quantize_kernel", "dequantize_kernel",
     "chunk_rows_kernel", "spmm_kernel", "spmm_fixup_kernel", "gemm_kernel<FWD>", "gemm_kernel<DW>",
     "reduce_slabs_kernel", "gemm_kernel<DM>", "spmm_sliced_kernel", "relu_mask_kernel", "test_encode_kernel",
-    "gather_codes_kernel"};
+    "gather_codes_kernel", "spmm_kernel<transform>"};
 constexpr int kProfCap = 8192;
 struct ProfRec {
   int id;

@@ -38,17 +38,55 @@ __global__ void chunk_rows_kernel(const int64_t* __restrict__ rowptr, int n_rows
   for (int64_t c = (a + kChunk - 1) / kChunk; c * kChunk < b; ++c) chunk_row[c] = r;
 }
 
-template <typename T, int EPV, int NP>
+// The dense transform of the layer applied to every finished row (Sec. 3.1, first equation as one
+// kernel): z = m W for the aggregated row m, W [dim x G] with G <= 64, kept in LDS.
+struct XformArgs {
+  const float* W;  // dim x G, row-major
+  float* Z;        // nullable, rows x G
+  float* H;        // nullable, rows x G: relu ? max(z, 0) : z
+  int G;
+  int relu;
+};
+
+// z[lane] = sum_f row[f] * W[f][lane] for lane < G, f ascending, one fused multiply-add each; `row` is
+// in LDS (every lane reads the same address: a broadcast), W in LDS or global memory.
+__device__ __forceinline__ void transform_row(const float* row, const float* W, int dim, const XformArgs& xf,
+                                              int64_t out_row, int lane) {
+  if (lane >= xf.G) return;
+  float z = 0.0f;
+  int f = 0;
+  for (; f + 4 <= dim; f += 4) {
+    const float4 m = *reinterpret_cast<const float4*>(row + f);
+    z = __fmaf_rn(m.x, W[(f + 0) * xf.G + lane], z);
+    z = __fmaf_rn(m.y, W[(f + 1) * xf.G + lane], z);
+    z = __fmaf_rn(m.z, W[(f + 2) * xf.G + lane], z);
+    z = __fmaf_rn(m.w, W[(f + 3) * xf.G + lane], z);
+  }
+  for (; f < dim; ++f) z = __fmaf_rn(row[f], W[f * xf.G + lane], z);
+  const int64_t at = out_row * xf.G + lane;
+  if (xf.Z) xf.Z[at] = z;
+  if (xf.H) xf.H[at] = xf.relu ? (z > 0.0f ? z : 0.0f) : z;
+}
+
+// LDS of the transforming variants: W, then one row buffer per wavefront (rows padded to 4 floats)
+__host__ __device__ inline int xf_row_floats(int dim) { return (dim + 3) / 4 * 4; }
+
+template <typename T, int EPV, int NP, bool XF = false>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
     const int64_t* __restrict__ rowptr, const int* __restrict__ colidx, const float* __restrict__ vals,
     int n_rows, int64_t nnz, const T* __restrict__ X, int64_t ldx, T* __restrict__ Y, T* __restrict__ Y2,
     int64_t ldy, int dim, const int* __restrict__ chunk_row, int64_t nchunks, float* __restrict__ phead, float* __restrict__ ptail,
-    int* __restrict__ tail_row, int kChunk) {
+    int* __restrict__ tail_row, int kChunk, XformArgs xf) {
   constexpr int U = (8 / NP) > 0 ? (8 / NP) : 1;  // feature rows in flight per wavefront
+  extern __shared__ __align__(16) float xf_lds[];
   const int lane = threadIdx.x & 63;
   // the wavefront index is the same in all lanes: say so, and everything derived from it
   // (chunk bounds, row cursor, loop counters) lives in scalar registers
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if constexpr (XF) {
+    for (int i = threadIdx.x; i < dim * xf.G; i += kSpmmThreads) xf_lds[i] = xf.W[i];
+    __syncthreads();
+  }
   const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + wave;
   if (chunk >= nchunks) return;
   const int64_t s = chunk * kChunk;
@@ -108,6 +146,21 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_kernel(
           for (int c = 0; c < EPV; ++c) pos[c] = acc[p][c] > 0.0f ? acc[p][c] : 0.0f;
           VecIO<T, EPV>::store(py + (p * 64 + lane) * EPV, pos);
         }
+    }
+    if constexpr (XF) {
+      // the finished row goes to this wavefront's LDS buffer, then every lane < G forms one output
+      float* rb = xf_lds + xf_row_floats(dim * xf.G) + wave * xf_row_floats(dim);
+#pragma unroll
+      for (int p = 0; p < NP; ++p)
+        if (col_on[p]) {
+#pragma unroll
+          for (int c = 0; c < EPV; ++c) rb[(p * 64 + lane) * EPV + c] = acc[p][c];
+        }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+      transform_row(rb, xf_lds, dim, xf, row, lane);
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the next row is written only after every lane has read this one
     }
   };
   auto store_partial = [&](float* buf) {
@@ -449,6 +502,39 @@ static int pick_chunk(int64_t nnz) {
   return c;
 }
 
+// The same for the transforming variant (fp32): the summed row is stored and then transformed (W from
+// global memory: only rows that straddle chunk borders come here).
+template <int EPV>
+__global__ __launch_bounds__(kSpmmThreads) void spmm_fixup_transform_kernel(
+    const int* __restrict__ chunk_row, const int* __restrict__ tail_row, int64_t nchunks,
+    const float* __restrict__ phead, const float* __restrict__ ptail, float* __restrict__ Y, int64_t ldy, int dim,
+    int n_rows, XformArgs xf) {
+  extern __shared__ __align__(16) float xf_lds[];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + wave;
+  if (chunk >= nchunks) return;
+  const int r = tail_row[chunk];
+  if (r < 0 || r >= n_rows) return;
+  int64_t last = chunk;
+  while (last + 1 < nchunks && chunk_row[last + 1] == r) ++last;
+  float* rb = xf_lds + wave * xf_row_floats(dim);
+  for (int col = lane * EPV; col < dim; col += 64 * EPV) {
+    float acc[EPV];
+#pragma unroll
+    for (int c = 0; c < EPV; ++c) acc[c] = ptail[chunk * static_cast<int64_t>(dim) + col + c];
+    for (int64_t c2 = chunk + 1; c2 <= last; ++c2)
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) acc[c] = acc[c] + phead[c2 * static_cast<int64_t>(dim) + col + c];
+    if (Y) VecIO<float, EPV>::store(Y + static_cast<int64_t>(r) * ldy + col, acc);
+#pragma unroll
+    for (int c = 0; c < EPV; ++c) rb[col + c] = acc[c];
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  transform_row(rb, xf.W, dim, xf, r, lane);
+}
+
 int64_t spmm_chunks(int64_t nnz) { return nnz <= 0 ? 1 : ceil_div(nnz, pick_chunk(nnz)); }
 
 // Upper bound of spmm_chunks over every matrix of at most nnz entries (the chunk size steps up with nnz,
@@ -498,6 +584,9 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, i
 #define CDF_SPMM_ARGS                                                                                      \
   (A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, Y2, ldy, dim, chunk_row, nc, phead, ptail, \
    tail_row, chunk)
+#define CDF_SPMM_ARGS_X                                                                                    \
+  (A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, Y, Y2, ldy, dim, chunk_row, nc, phead, ptail, \
+   tail_row, chunk, XformArgs{})
   // Lanes per entry. Rows of whole 128-byte lines with eight or more entries on average: one line per
   // row and slice (8 lanes of 16 bytes); it pays when the per-row, per-slice reduction and store are
   // amortised. Rows of at most 32 lane-vectors: one slice, the lane group just wide enough for the row.
@@ -534,14 +623,15 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, i
     }
   } else {
     prof_begin(K_SPMM, st);
-    if (np <= 1) spmm_kernel<T, EPV, 1><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
-    else if (np <= 2) spmm_kernel<T, EPV, 2><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
-    else if (np <= 4) spmm_kernel<T, EPV, 4><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
-    else spmm_kernel<T, EPV, 8><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS;
+    if (np <= 1) spmm_kernel<T, EPV, 1><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS_X;
+    else if (np <= 2) spmm_kernel<T, EPV, 2><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS_X;
+    else if (np <= 4) spmm_kernel<T, EPV, 4><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS_X;
+    else spmm_kernel<T, EPV, 8><<<nblocks, kSpmmThreads, 0, st>>> CDF_SPMM_ARGS_X;
     prof_end(K_SPMM, st);
     CDF_LAUNCH_CHECK("cdf_spmm/main");
   }
 #undef CDF_SPMM_ARGS
+#undef CDF_SPMM_ARGS_X
   {
     ProfScope ps(K_SPMM_FIXUP, st);
     spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, Y2, ldy, dim,
@@ -599,9 +689,91 @@ int spmm_run(const char* fn, const cdf_csr* A, const void* X, int64_t ldx, void*
   return CDF_OK;
 }
 
+int dense_fwd_ws(const void* M, int64_t ldm, cdf_dtype dt, const float* W, int32_t n, int32_t f_in, int32_t f_out,
+                 int relu, float* Z, float* H, void* ws, size_t ws_bytes, void* stream);
+
+// Can the aggregation carry the dense transform in its row epilogue? fp32 rows read as 16-byte lane
+// vectors, at most 64 output columns, W and four row buffers within 64 KB of LDS.
+bool spmm_transform_ok(const void* X, int64_t ldx, const void* M, int64_t ldm, int32_t dim, int32_t g, cdf_dtype dt) {
+  if (dt != CDF_F32 || dim % 4 != 0 || ldx % 4 != 0 || ldm % 4 != 0 || !aligned(X, 16) || !aligned(M, 16)) return false;
+  if (g < 1 || g > 64 || dim > 1024) return false;
+  const size_t lds = (static_cast<size_t>(xf_row_floats(dim * g)) + kSpmmWaves * xf_row_floats(dim)) * sizeof(float);
+  return lds <= 65536;
+}
+
+// M = A X, Z = M W, H = sigma(Z) in one pass over the matrix (plus the fix-up of straddling rows).
+int spmm_transform_run(const char* fn, const cdf_csr* A, const float* X, int64_t ldx, const float* W, int32_t dim,
+                       int32_t g, int relu, float* M, int64_t ldm, float* Z, float* H, void* ws, size_t ws_bytes,
+                       hipStream_t st) {
+  CDF_REQUIRE(A != nullptr && A->n_rows >= 0 && A->nnz >= 0, "%s: bad matrix", fn);
+  if (A->n_rows == 0) return CDF_OK;
+  CDF_REQUIRE(A->rowptr && M && W && (Z || H) && (A->nnz == 0 || (A->colidx && A->vals && X)), "%s: null pointer", fn);
+  CDF_REQUIRE(aligned(A->rowptr, 8) && aligned(W, 4) && aligned(Z, 4) && aligned(H, 4), "%s: misaligned pointer", fn);
+  if (!ws || !aligned(ws, 256) || ws_bytes < spmm_workspace_bytes(A->nnz, dim))
+    CDF_FAIL(CDF_ERR_WORKSPACE, "%s: workspace too small or unaligned (%zu < %zu)", fn, ws_bytes,
+             spmm_workspace_bytes(A->nnz, dim));
+  const int chunk = pick_chunk(A->nnz);
+  const int64_t nc = spmm_chunks(A->nnz);
+  char* w = static_cast<char*>(ws);
+  int* own_chunk_row = reinterpret_cast<int*>(w);
+  int* tail_row = own_chunk_row + nc;
+  w += align_up(static_cast<size_t>(nc) * 2 * sizeof(int), 256);
+  float* phead = reinterpret_cast<float*>(w);
+  w += align_up(static_cast<size_t>(nc) * dim * sizeof(float), 256);
+  float* ptail = reinterpret_cast<float*>(w);
+  const int* chunk_row = A->plan;
+  if (!chunk_row) {
+    {
+      ProfScope ps(K_SPMM_PLAN, st);
+      chunk_rows_kernel<<<static_cast<unsigned>(ceil_div(A->n_rows, 256)), 256, 0, st>>>(A->rowptr, A->n_rows,
+                                                                                         own_chunk_row, chunk);
+    }
+    CDF_LAUNCH_CHECK("spmm + transform/chunk_rows");
+    chunk_row = own_chunk_row;
+  }
+  const unsigned nblocks = static_cast<unsigned>(ceil_div(nc, kSpmmWaves));
+  const XformArgs xf = {W, Z, H, g, relu ? 1 : 0};
+  const size_t lds_main = (static_cast<size_t>(xf_row_floats(dim * g)) + kSpmmWaves * xf_row_floats(dim)) * sizeof(float);
+  const size_t lds_fix = static_cast<size_t>(kSpmmWaves) * xf_row_floats(dim) * sizeof(float);
+  const int np = static_cast<int>(ceil_div(dim, 256));
+  float* none = nullptr;
+#define CDF_XF_ARGS                                                                                              \
+  (A->rowptr, A->colidx, A->vals, A->n_rows, A->nnz, X, ldx, M, none, ldm, dim, chunk_row, nc, phead, ptail, tail_row, \
+   chunk, xf)
+  prof_begin(K_SPMM_XFORM, st);
+  if (np <= 1) spmm_kernel<float, 4, 1, true><<<nblocks, kSpmmThreads, lds_main, st>>> CDF_XF_ARGS;
+  else if (np <= 2) spmm_kernel<float, 4, 2, true><<<nblocks, kSpmmThreads, lds_main, st>>> CDF_XF_ARGS;
+  else spmm_kernel<float, 4, 4, true><<<nblocks, kSpmmThreads, lds_main, st>>> CDF_XF_ARGS;
+  prof_end(K_SPMM_XFORM, st);
+#undef CDF_XF_ARGS
+  CDF_LAUNCH_CHECK("spmm + transform/main");
+  {
+    ProfScope ps(K_SPMM_FIXUP, st);
+    spmm_fixup_transform_kernel<4><<<nblocks, kSpmmThreads, lds_fix, st>>>(chunk_row, tail_row, nc, phead, ptail, M, ldm,
+                                                                           dim, A->n_rows, xf);
+  }
+  CDF_LAUNCH_CHECK("spmm + transform/fixup");
+  return CDF_OK;
+}
+
 }  // namespace cdf
 
 using namespace cdf;
+
+extern "C" int cdf_spmm_dense_fwd(const cdf_csr* A, const void* X, int64_t ldx, cdf_dtype dt, const float* W,
+                                  int32_t f_in, int32_t f_out, int relu, void* M, int64_t ldm, float* Z, float* H,
+                                  void* ws, size_t ws_bytes, void* stream) {
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  CDF_REQUIRE(A != nullptr && f_in > 0 && f_out > 0 && ldx >= f_in && ldm >= f_in,
+              "cdf_spmm_dense_fwd: bad shape f_in=%d f_out=%d ldx=%lld ldm=%lld", f_in, f_out, (long long)ldx,
+              (long long)ldm);
+  if (spmm_transform_ok(X, ldx, M, ldm, f_in, f_out, dt))
+    return spmm_transform_run("cdf_spmm_dense_fwd", A, static_cast<const float*>(X), ldx, W, f_in, f_out, relu,
+                              static_cast<float*>(M), ldm, Z, H, ws, ws_bytes, st);
+  const int rc = spmm_run("cdf_spmm_dense_fwd", A, X, ldx, M, nullptr, ldm, f_in, dt, ws, ws_bytes, st);
+  if (rc != CDF_OK) return rc;
+  return dense_fwd_ws(M, ldm, dt, W, A->n_rows, f_in, f_out, relu, Z, H, ws, ws_bytes, stream);
+}
 
 extern "C" int cdf_spmm_fwd(const cdf_csr* A, const void* X, int64_t ldx, void* Y, int64_t ldy, int32_t dim,
                             cdf_dtype dt, void* ws, size_t ws_bytes, void* stream) {

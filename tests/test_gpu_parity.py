@@ -410,6 +410,70 @@ def test_spmm_padded_pitch_long_rows(cdf, oracle):
         assert_rows_close(to_np(Y.contiguous()), want, what=f"Y dim {dim}")
 
 
+@pytest.mark.parametrize("f_in,f_out", [(128, 16), (16, 8), (256, 41), (256, 47), (100, 47), (512, 24), (1024, 12),
+                                        (64, 64), (4, 1), (256, 64), (128, 70), (37, 8)])
+@pytest.mark.parametrize("relu", [True, False])
+def test_spmm_dense_fwd_one_kernel(cdf, oracle, f_in, f_out, relu):
+    """Aggregation with the dense transform in its row epilogue (narrow outputs) and its two-launch
+    fall-back (256 x 64 needs more LDS than a block has, 70 columns are too many, 37 is not a multiple of
+    four): M, Z, H against the oracle's aggregation followed by its transform; two runs bit-equal."""
+    P = configs.build_partition(configs.TINY)
+    n, nc = P.n_loc, P.n_loc + P.n_halo
+    X = features.normal_matrix(5, f_in, nc, f_in)
+    W = features.glorot(5, f_out, f_in, f_out)
+    A = cdf.DeviceCsr(n, nc, P.rowptr, P.colidx, P.vals, DEV)
+    ws = ws_for(cdf, nc, max(f_in, f_out), P.nnz)
+    outs = []
+    for _ in range(2):
+        M = torch.full((n, f_in), 3.0, device=DEV)
+        Z = torch.full((n, f_out), 3.0, device=DEV)
+        H = torch.full((n, f_out), 3.0, device=DEV)
+        cdf.cdf_spmm_dense_fwd(A.struct, X.to(DEV), W.to(DEV), relu, M, Z, H, ws)
+        torch.cuda.synchronize()
+        outs.append((M, Z, H))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    oM = oracle.spmm(*csr_np(P), nc, X.numpy())
+    oZ, oH = oracle.dense_fwd(oM, W.numpy(), relu)
+    M, Z, H = outs[0]
+    assert_rows_close(to_np(M), oM, what="M")
+    assert_rows_close(to_np(Z), oZ, what="Z")
+    assert_rows_close(to_np(H), oH, what="H")
+    # H alone (the layer step keeps no Z)
+    H2 = torch.full((n, f_out), 3.0, device=DEV)
+    cdf.cdf_spmm_dense_fwd(A.struct, X.to(DEV), W.to(DEV), relu, M, None, H2, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(H2, H)
+
+
+def test_spmm_dense_fwd_long_and_empty_rows(cdf, oracle):
+    """Rows that straddle chunk borders take the fix-up route of the one-kernel call; empty rows give zeros."""
+    rs = np.random.default_rng(23)
+    lens = [0, 0, 1, 255, 0, 64, 0, 65, 3, 5000, 0, 63, 2, 1, 700, 0, 0, 1280, 0, 31, 0]
+    n_cols = 4000
+    rowptr = np.zeros(len(lens) + 1, np.int64)
+    rowptr[1:] = np.cumsum(lens)
+    colidx = np.concatenate([np.sort(rs.choice(n_cols, l, replace=l > n_cols)) for l in lens]).astype(np.int32)
+    vals = rs.standard_normal(colidx.size).astype(np.float32)
+    for f_in, f_out in ((128, 16), (256, 47), (512, 8)):
+        X = torch.from_numpy(rs.standard_normal((n_cols, f_in)).astype(np.float32))
+        W = torch.from_numpy((rs.standard_normal((f_in, f_out)) * 0.1).astype(np.float32))
+        A = cdf.DeviceCsr(len(lens), n_cols, torch.from_numpy(rowptr), torch.from_numpy(colidx), torch.from_numpy(vals), DEV)
+        ws = ws_for(cdf, n_cols, f_in, colidx.size)
+        M = torch.full((len(lens), f_in), 3.0, device=DEV)
+        Z = torch.full((len(lens), f_out), 3.0, device=DEV)
+        H = torch.full((len(lens), f_out), 3.0, device=DEV)
+        cdf.cdf_spmm_dense_fwd(A.struct, X.to(DEV), W.to(DEV), True, M, Z, H, ws)
+        torch.cuda.synchronize()
+        oM = oracle.spmm(rowptr, colidx, vals, n_cols, X.numpy())
+        oZ, oH = oracle.dense_fwd(oM, W.numpy(), True)
+        assert_rows_close(to_np(M), oM, what="M")
+        assert_rows_close(to_np(Z), oZ, what="Z")
+        assert_rows_close(to_np(H), oH, what="H")
+        empty = [i for i, l in enumerate(lens) if l == 0]
+        assert int((Z[empty] != 0).sum().item()) == 0 and int((H[empty] != 0).sum().item()) == 0
+
+
 DENSE_SHAPES = [(1000, 100, 47), (300, 602, 256), (513, 16, 8), (700, 128, 256), (257, 256, 41), (130, 64, 64),
                 (5000, 128, 16), (64, 33, 130), (4096, 128, 256), (2048, 256, 64), (1024, 64, 128)]
 
