@@ -84,9 +84,25 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
   int Mdim, Ndim, Kbeg, Kend;
   if (MODE == GEMM_FWD) { Mdim = a.n; Ndim = a.g; Kbeg = 0; Kend = a.f; }
   else if (MODE == GEMM_DM) { Mdim = a.n; Ndim = a.f; Kbeg = 0; Kend = a.g; }
-  else { Mdim = a.f; Ndim = a.g; Kbeg = blockIdx.z * a.slab_rows; Kend = min(a.n, Kbeg + a.slab_rows); }
-  const int m0 = blockIdx.x * kBM;
-  const int n0 = blockIdx.y * BN;
+  else { Mdim = a.f; Ndim = a.g; Kbeg = 0; Kend = 0; }
+  // FWD / DM: grid (row tiles, column tiles). DW: a 1-D grid decoded so that the tiles of one row slab
+  // (which share the slab's M rows and dZ rows) carry workgroup ids that are equal modulo 8 and follow
+  // each other closely: workgroups go to the eight XCDs round-robin, so the slab's operands are then
+  // fetched into one L2 once instead of into several.
+  int tile_m = blockIdx.x, tile_n = blockIdx.y, slab = 0;
+  if (MODE == GEMM_DW) {
+    const int tiles_m = (a.f + kBM - 1) / kBM, tiles_n = (a.g + BN - 1) / BN, tiles = tiles_m * tiles_n;
+    const int group = blockIdx.x / (8 * tiles), within = blockIdx.x % (8 * tiles);
+    const int t = within / 8;
+    slab = group * 8 + within % 8;
+    if (static_cast<int64_t>(slab) * a.slab_rows >= a.n) return;   // padding of the last group (uniform per block)
+    tile_m = t % tiles_m;
+    tile_n = t / tiles_m;
+    Kbeg = slab * a.slab_rows;
+    Kend = min(a.n, Kbeg + a.slab_rows);
+  }
+  const int m0 = tile_m * kBM;
+  const int n0 = tile_n * BN;
 
   const T* Ap = static_cast<const T*>(a.A);
   const float* dHp = static_cast<const float*>(a.A);
@@ -265,7 +281,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
           float one[1] = {v};
           VecIO<T, 1>::store(o, one);
         } else {
-          a.out0[(static_cast<int64_t>(blockIdx.z) * a.f + row) * a.g + col] = v;
+          a.out0[(static_cast<int64_t>(slab) * a.f + row) * a.g + col] = v;
         }
       }
     }
@@ -323,7 +339,9 @@ static void launch_gemm(const GemmArgs& a, int Mdim, int Ndim, int slabs, int a_
   const int Kdim = MODE == GEMM_FWD ? a.f : MODE == GEMM_DM ? a.g : a.slab_rows;
   const bool k_full = Kdim % kBK == 0 && (MODE != GEMM_DW || a.n % a.slab_rows == 0);
   const bool fast = Mdim % kBM == 0 && Ndim % bn == 0 && k_full && a_vec && b_vec && (!a.relu || MODE == GEMM_FWD || m_vec);
-  dim3 grid(static_cast<unsigned>(ceil_div(Mdim, kBM)), static_cast<unsigned>(ceil_div(Ndim, bn)), slabs);
+  dim3 grid(static_cast<unsigned>(ceil_div(Mdim, kBM)), static_cast<unsigned>(ceil_div(Ndim, bn)), 1);
+  if (MODE == GEMM_DW)   // 1-D: groups of eight slabs, all tiles of a slab on ids that are equal modulo 8
+    grid = dim3(static_cast<unsigned>(ceil_div(slabs, 8) * 8 * grid.x * grid.y), 1, 1);
   if (bn == 256) {
     if (fast) gemm_kernel<T, MODE, 256, true><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
     else gemm_kernel<T, MODE, 256, false><<<grid, kGemmThreads, 0, st>>>(a, a_vec, b_vec, m_vec);
