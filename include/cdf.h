@@ -169,6 +169,10 @@ int cdf_quantize(const void* cur, void* cached, const int32_t* idx, const int32_
                  int32_t max_sent, int32_t dim, int64_t ld, cdf_dtype dt, int bits, cdf_qscheme qs,
                  cdf_commit commit, int delta, uint8_t* codes, float* meta, void* stream);
 
+/* Host-side test hook: the number of polls after which a workgroup of the look-back route above gives
+ * up waiting for its predecessors (polls <= 0 restores the default of about a million). */
+int cdf_set_message_wait_limit(int polls);
+
 /*
  * Message recovery (Sec. 5, second equation) and the receiver's cache update (Alg. 2,
  * message loop: cached_total <- cached_total + delta). For k < *n_sent:
@@ -186,10 +190,16 @@ int cdf_dequantize(const uint8_t* codes, const float* meta, const int32_t* idx, 
 /*
  * cdf_cache_filter followed by cdf_quantize on the same rows, in one pass over them where that is
  * possible (quantised messages, ws of cdf_workspace_bytes(n_rows, dim, 0) or more):
- * a row is read once, tested, and - if it fails - coded and committed from the same registers; the
- * messages are then moved into rank order. In every other case the two calls run one after the
- * other. mask, idx, *n_sent, codes, meta and the committed cache are bit-identical to the two
- * calls either way. Arguments as for those calls; capacity of idx / codes / meta = n_rows.
+ * a row is read once, tested, and - if it fails - coded and committed from the same registers.
+ * Small inputs (all workgroups resident at once, some ten thousand rows) write every message
+ * straight to its place: a workgroup learns the number of sent rows before its own from its
+ * predecessors through status words in the workspace (single-pass scan with look-back; a workgroup
+ * publishes its count before it waits, the wait is bounded). Larger inputs stage the messages by row
+ * and move them into rank order with a second small kernel. In every other case the two calls run one
+ * after the other. mask, idx, *n_sent, codes, meta and the committed cache are bit-identical to the
+ * two calls on every route. Arguments as for those calls; capacity of idx / codes / meta = n_rows.
+ * Should the bounded wait ever expire (never seen; it needs a workgroup that is not scheduled for
+ * about a second), *n_sent is -1, which every consumer in this library treats as "no messages".
  */
 int cdf_cache_filter_quantize(const void* cur, void* cached, int32_t n_rows, int32_t dim, int64_t ld,
                               cdf_dtype dt, float eps, cdf_norm norm, int bits, cdf_qscheme qs,

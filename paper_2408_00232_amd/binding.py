@@ -23,7 +23,7 @@ COMMIT_NONE, COMMIT_CUR, COMMIT_DEQ = 0, 1, 2
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ["cdf_profile_copy", "cdf_profile_enable", "cdf_profile_kernels", "cdf_profile_kernel_name", "cdf_profile_read", "cdf_profile_read_all",
-           "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_max_message_dim", "cdf_cache_filter", "cdf_cache_filter_static", "cdf_quantize", "cdf_cache_filter_quantize",
+           "cdf_last_error", "cdf_workspace_bytes", "cdf_code_row_bytes", "cdf_max_message_dim", "cdf_cache_filter", "cdf_cache_filter_static", "cdf_quantize", "cdf_cache_filter_quantize", "cdf_set_message_wait_limit",
            "cdf_dequantize", "cdf_spmm_plan_bytes", "cdf_spmm_plan", "cdf_spmm_fwd", "cdf_spmm_bwd", "cdf_spmm_dense_fwd", "cdf_dense_fwd", "cdf_dense_bwd",
            "cdf_gcn_layer_fwd", "cdf_gcn_layer_bwd", "cdf_gcn_layer_tf_fwd", "cdf_gcn_layer_tf_bwd",
            "cdf_softmax_xent", "cdf_adam_step", "cdf_accumulate", "cdf_gather_rows", "cdf_map_index",
@@ -252,6 +252,10 @@ def cdf_cache_filter_quantize(cur, cached, eps, norm, bits, qs, commit, delta, m
                                           ctypes.c_int(1 if delta else 0), _ptr(mask), _ptr(idx), _ptr(n_sent), _ptr(codes),
                                           _ptr(meta), _ptr(ws), ctypes.c_size_t(ws.numel() * ws.element_size()), _stream())
     _check("cdf_cache_filter_quantize", rc)
+
+
+def cdf_set_message_wait_limit(polls: int) -> None:
+    _check("cdf_set_message_wait_limit", load().cdf_set_message_wait_limit(ctypes.c_int(polls)))
 
 
 def cdf_dequantize(codes, meta, idx, n_sent, max_sent, bits, qs, dst, accumulate):

@@ -291,6 +291,227 @@ __global__ __launch_bounds__(kQuantThreads) void test_encode_kernel(
   }
 }
 
+// ---- cache test and message build in one pass, every message written once, in its place -------------
+// The rank of a sent row among all sent rows is its position in idx / codes / meta. Here the wavefronts
+// of a workgroup hold their rows in registers, count how many of them fail the test, and the workgroup
+// learns the number of sent rows before its first one from the workgroups before it through a chain of
+// status words in device memory (a single-pass scan with look-back): workgroup e publishes its own
+// count at once, then its first wavefront reads back over the predecessors' words - counts of those
+// that do not know their prefix yet, the prefix of the first one that does - and publishes its own
+// prefix. The wavefronts then code their sent rows straight into rows k, k+1, ... of the outputs from
+// the registers they still hold.
+//
+// Progress: workgroups are dispatched in the order of their ids and a workgroup publishes its count
+// before it waits, so the workgroups it waits for are resident or finished. The wait is bounded all the
+// same: after `spin_limit` polls a workgroup gives up, marks its word, and every later workgroup that
+// meets the mark does the same; *n_sent is then -1 and the rows from there on are neither coded nor
+// committed. Every wavefront reaches its end either way.
+constexpr int kChainEmpty = 0, kChainCount = 1, kChainPrefix = 2, kChainGaveUp = 3;
+
+__device__ __forceinline__ unsigned long long chain_word(int state, int value) {
+  return (static_cast<unsigned long long>(static_cast<unsigned>(state)) << 32) | static_cast<unsigned>(value);
+}
+
+// Steps of rows a wavefront holds at once: about 32 values of x and of z per lane.
+__host__ __device__ constexpr int chain_steps(int per_lane) {
+  return per_lane >= 32 ? 1 : per_lane >= 16 ? 2 : per_lane >= 8 ? 4 : 8;
+}
+
+__global__ __launch_bounds__(256) void chain_clear_kernel(unsigned long long* __restrict__ status, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) status[i] = 0ull;
+}
+
+template <typename T, int EPV, int NIT, int BITS, int QS>
+__global__ __launch_bounds__(kQuantThreads) void test_encode_chained_kernel(
+    const T* __restrict__ cur, T* cached, int n_rows, int dim, int64_t ld, float eps, int norm, int glog, int commit,
+    int delta, uint8_t* __restrict__ mask, int* __restrict__ idx, int* __restrict__ n_sent,
+    uint8_t* __restrict__ codes, float* __restrict__ meta, unsigned long long* status, int n_elems, int spin_limit) {
+  constexpr int NACC = 4 / EPV;
+  constexpr int S = chain_steps(NIT * EPV);
+  constexpr int kWaves = kQuantThreads / 64;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int e = blockIdx.x;   // this workgroup's place in the chain (its wavefronts take consecutive rows)
+  const int G = 1 << glog;
+  const int lg = lane & (G - 1), sub = lane >> glog;
+  const int rows_per_step = 64 >> glog;
+  const int nvec = dim / EPV;
+  const int64_t rb = (static_cast<int64_t>(dim) * BITS + 7) / 8;
+  const int row0 = (e * kWaves + wave) * (S * rows_per_step);
+
+  float x[S][NIT][EPV], z[S][NIT][EPV];
+  bool send[S];
+  unsigned long long bits[S];
+  int count = 0;
+#pragma unroll
+  for (int s = 0; s < S; ++s) {
+    const int row = row0 + s * rows_per_step + sub;
+    const bool live = row < n_rows;
+    const int64_t r = live ? row : 0;
+    const T* pc = cur + r * ld;
+    const T* pz = cached + r * ld;
+#pragma unroll
+    for (int i = 0; i < NIT; ++i) {
+      const int v = lg + i * G;
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) x[s][i][c] = z[s][i][c] = 0.0f;
+      if (live && v < nvec) {
+        VecIO<T, EPV>::load(pc + static_cast<int64_t>(v) * EPV, x[s][i]);
+        VecIO<T, EPV>::load(pz + static_cast<int64_t>(v) * EPV, z[s][i]);
+      }
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < S; ++s) {
+    const int row = row0 + s * rows_per_step + sub;
+    const bool live = row < n_rows;
+    // the test, in the cache test's own order of operations (masks must agree bit for bit)
+    float D, C, thr;
+    if (norm == CDF_NORM_LINF) {
+      D = 0.0f;
+      C = 0.0f;
+#pragma unroll
+      for (int i = 0; i < NIT; ++i)
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) {
+          D = fmaxf(D, fabsf(x[s][i][c] - z[s][i][c]));
+          C = fmaxf(C, fabsf(z[s][i][c]));
+        }
+      D = group_max(D, G);
+      C = group_max(C, G);
+      thr = eps * C;
+    } else {
+      float ad[NACC][EPV], ac[NACC][EPV];
+#pragma unroll
+      for (int a = 0; a < NACC; ++a)
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) ad[a][c] = ac[a][c] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < NIT; ++i)
+#pragma unroll
+        for (int c = 0; c < EPV; ++c) {
+          const float d = x[s][i][c] - z[s][i][c];
+          ad[i % NACC][c] = __fmaf_rn(d, d, ad[i % NACC][c]);
+          ac[i % NACC][c] = __fmaf_rn(z[s][i][c], z[s][i][c], ac[i % NACC][c]);
+        }
+      float Da[NACC], Ca[NACC];
+#pragma unroll
+      for (int a = 0; a < NACC; ++a) {
+        float d, c;
+        if (EPV == 4) {
+          d = (ad[a][0] + ad[a][1 % EPV]) + (ad[a][2 % EPV] + ad[a][3 % EPV]);
+          c = (ac[a][0] + ac[a][1 % EPV]) + (ac[a][2 % EPV] + ac[a][3 % EPV]);
+        } else if (EPV == 2) {
+          d = ad[a][0] + ad[a][1 % EPV];
+          c = ac[a][0] + ac[a][1 % EPV];
+        } else {
+          d = ad[a][0];
+          c = ac[a][0];
+        }
+        Da[a] = group_sum(d, G);
+        Ca[a] = group_sum(c, G);
+      }
+      if (NACC == 4) {
+        D = (Da[0] + Da[1 % NACC]) + (Da[2 % NACC] + Da[3 % NACC]);
+        C = (Ca[0] + Ca[1 % NACC]) + (Ca[2 % NACC] + Ca[3 % NACC]);
+      } else if (NACC == 2) {
+        D = Da[0] + Da[1 % NACC];
+        C = Ca[0] + Ca[1 % NACC];
+      } else {
+        D = Da[0];
+        C = Ca[0];
+      }
+      const float e2 = eps * eps;
+      thr = e2 * C;
+    }
+    send[s] = live && D > thr;
+    const bool head = live && lg == 0;
+    if (head) mask[row] = send[s] ? 1 : 0;
+    bits[s] = __ballot(head && send[s]);
+    count += __popcll(bits[s]);
+  }
+
+  // ---- the chain: sent rows before this workgroup's first row (looked up by its first wavefront) ----
+  __shared__ int wave_count[kWaves];
+  __shared__ int block_before;   // -1: gave up
+  if (lane == 0) wave_count[wave] = count;
+  __syncthreads();
+  int block_count = 0, wave_before = 0;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) {
+    const int c = wave_count[w];
+    if (w < wave) wave_before += c;
+    block_count += c;
+  }
+  if (wave == 0) {
+    int before = 0;
+    bool gave_up = false;
+    if (e == 0) {
+      if (lane == 0)
+        __hip_atomic_store(status, chain_word(kChainPrefix, block_count), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+      if (lane == 0)
+        __hip_atomic_store(status + e, chain_word(kChainCount, block_count), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      int pos = e - 1, polls = 0;
+      while (true) {
+        const int i = pos - lane;   // lane l looks at the l-th workgroup back from pos; past the start counts as prefix 0
+        const unsigned long long w = i >= 0 ? __hip_atomic_load(status + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                            : chain_word(kChainPrefix, 0);
+        const int state = static_cast<int>(w >> 32);
+        const unsigned long long known = __ballot(state == kChainPrefix);
+        const int first = known != 0ull ? __builtin_ctzll(known) : 64;   // nearest workgroup that knows its prefix
+        const unsigned long long needed = first >= 63 ? ~0ull : (2ull << first) - 1ull;   // lanes 0 .. first
+        if ((__ballot(state == kChainGaveUp) & needed) != 0ull) {
+          gave_up = true;
+          break;
+        }
+        if ((__ballot(state == kChainEmpty) & needed) != 0ull) {
+          if (++polls > spin_limit) {
+            gave_up = true;
+            break;
+          }
+          __builtin_amdgcn_s_sleep(2);
+          continue;
+        }
+        int v = lane <= first ? static_cast<int>(static_cast<unsigned>(w)) : 0;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off, kWave);
+        before += v;
+        if (first < 64) break;
+        pos -= 64;
+      }
+      if (lane == 0)
+        __hip_atomic_store(status + e, gave_up ? chain_word(kChainGaveUp, 0) : chain_word(kChainPrefix, before + block_count),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (lane == 0) {
+      block_before = gave_up ? -1 : before;
+      if (e == n_elems - 1) *n_sent = gave_up ? -1 : before + block_count;
+    }
+  }
+  __syncthreads();
+  if (block_before < 0) return;
+  int before = block_before + wave_before;
+
+  // ---- code and commit the sent rows, in place ----
+#pragma unroll
+  for (int s = 0; s < S; ++s) {
+    const int row = row0 + s * rows_per_step + sub;
+    const int64_t r = send[s] ? row : 0;
+    const int64_t k = send[s] ? before + __popcll(bits[s] & ((1ull << (sub << glog)) - 1ull)) : 0;
+    float m[NIT][EPV];
+#pragma unroll
+    for (int i = 0; i < NIT; ++i)
+#pragma unroll
+      for (int c = 0; c < EPV; ++c) m[i][c] = delta ? x[s][i][c] - z[s][i][c] : x[s][i][c];
+    if (send[s] && lg == 0) idx[k] = row;
+    encode_row<T, EPV, NIT, BITS, QS>(send[s], lg, G, nvec, x[s], z[s], m, commit, delta, codes + k * rb, meta + 2 * k,
+                                      cached + r * ld);
+    before += __popcll(bits[s]);
+  }
+}
+
 // codes[k] = scratch[idx[k]], meta[k] = meta_scratch[idx[k]] for k < *n_sent, rows of rb bytes moved
 // in units of U bytes by groups of 16 lanes.
 template <typename U>
@@ -525,6 +746,13 @@ namespace cdf {
 // enough (test_encode_workspace_bytes); otherwise cdf_cache_filter then cdf_quantize. Both routes
 // compute every row with the same instruction sequence: mask, idx, codes, meta and the committed
 // cache are bit-identical.
+static int g_chain_spin_limit = 1 << 20;   // polls of a workgroup's bounded wait for its predecessors
+// The chained kernel is taken while all its workgroups are resident together (inputs of up to some ten
+// thousand rows): there it saves two launches and the second pass over the messages. On larger inputs
+// the wait for the predecessors costs more latency hiding than the second pass costs bandwidth
+// (measured 1.2 to 1.6 times slower from 250 000 rows on), so those stage the messages by row.
+constexpr int kChainMaxElems = 2048;
+
 int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, int64_t ld, cdf_dtype dt, float eps,
                     cdf_norm norm, int bits, cdf_qscheme qs, cdf_commit commit, int delta, uint8_t* mask, int32_t* idx,
                     int32_t* n_sent, uint8_t* codes, float* meta, void* ws, size_t ws_bytes, void* stream) {
@@ -537,11 +765,39 @@ int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, 
                         (commit == CDF_COMMIT_NONE || commit == CDF_COMMIT_CUR || commit == CDF_COMMIT_DEQ);
   const bool one_pass = types_ok && ws && aligned(ws, 256) && ws_bytes >= test_encode_workspace_bytes(n_rows, dim) &&
                         aligned(cur, esz) && aligned(cached, esz) && aligned(meta, 8) && aligned(codes, 16) &&
-                        row_shape(dim, pick_epv(dim, ld, esz, cur, cached), &s);
+                        aligned(idx, 4) && aligned(n_sent, 4) && row_shape(dim, pick_epv(dim, ld, esz, cur, cached), &s);
   if (!one_pass) {
     const int rc = cdf_cache_filter(cur, cached, n_rows, dim, ld, dt, eps, norm, mask, idx, n_sent, ws, ws_bytes, stream);
     if (rc != CDF_OK) return rc;
     return cdf_quantize(cur, cached, idx, n_sent, n_rows, dim, ld, dt, bits, qs, commit, delta, codes, meta, stream);
+  }
+  // every message written once, in its place: the chained kernel (see test_encode_chained_kernel)
+  const int chain_rows = (kQuantThreads / 64) * chain_steps(s.nit * s.epv) * (64 >> s.glog);   // rows per workgroup
+  const int n_elems = static_cast<int>(ceil_div(n_rows, chain_rows));
+  if (n_elems <= kChainMaxElems && ws_bytes >= align_up(static_cast<size_t>(n_elems) * 8, 256)) {
+    unsigned long long* status = static_cast<unsigned long long*>(ws);
+    {
+      ProfScope ps(K_SCAN, st);
+      chain_clear_kernel<<<static_cast<unsigned>(ceil_div(n_elems, 256)), 256, 0, st>>>(status, n_elems);
+    }
+    CDF_LAUNCH_CHECK("test_and_encode/clear");
+    const unsigned grid = static_cast<unsigned>(n_elems);
+#define ARGS_CH(T) <<<grid, kQuantThreads, 0, st>>>(static_cast<const T*>(cur), static_cast<T*>(cached), n_rows, dim, ld, \
+                 eps, (int)norm, s.glog, (int)commit, delta ? 1 : 0, mask, idx, n_sent, codes, meta, status, n_elems, \
+                 g_chain_spin_limit)
+#define CDF_DISPATCH_CH(K, T, ...)                                                                         \
+  if (qs == CDF_Q_MINMAX && bits == 8) { CDF_DISPATCH_EPV(K, T, 8, CDF_Q_MINMAX, s.epv, s.nit, __VA_ARGS__) } \
+  else if (qs == CDF_Q_MINMAX) { CDF_DISPATCH_EPV(K, T, 4, CDF_Q_MINMAX, s.epv, s.nit, __VA_ARGS__) }      \
+  else if (bits == 8) { CDF_DISPATCH_EPV(K, T, 8, CDF_Q_SYMMETRIC, s.epv, s.nit, __VA_ARGS__) }            \
+  else { CDF_DISPATCH_EPV(K, T, 4, CDF_Q_SYMMETRIC, s.epv, s.nit, __VA_ARGS__) }
+    prof_begin(K_TEST_ENCODE, st);
+    if (dt == CDF_F32) { CDF_DISPATCH_CH(test_encode_chained_kernel, float, ARGS_CH(float)) }
+    else { CDF_DISPATCH_CH(test_encode_chained_kernel, bf16_t, ARGS_CH(bf16_t)) }
+    prof_end(K_TEST_ENCODE, st);
+#undef ARGS_CH
+#undef CDF_DISPATCH_CH
+    CDF_LAUNCH_CHECK("test_and_encode/chained");
+    return CDF_OK;
   }
   const int nblocks = static_cast<int>(ceil_div(n_rows, kTestRows));
   char* w = static_cast<char*>(ws);
@@ -582,6 +838,11 @@ int test_and_encode(const void* cur, void* cached, int32_t n_rows, int32_t dim, 
 }
 
 }  // namespace cdf
+
+extern "C" int cdf_set_message_wait_limit(int polls) {
+  cdf::g_chain_spin_limit = polls > 0 ? polls : 1 << 20;
+  return CDF_OK;
+}
 
 extern "C" int cdf_cache_filter_quantize(const void* cur, void* cached, int32_t n_rows, int32_t dim, int64_t ld,
                                          cdf_dtype dt, float eps, cdf_norm norm, int bits, cdf_qscheme qs,

@@ -946,6 +946,43 @@ def test_cache_filter_quantize_equals_the_two_calls(dtype, dim, bits, qs, norm):
             assert (a == b) if isinstance(a, int) else torch.equal(a, b)
 
 
+def test_look_back_wait_is_bounded(cdf, oracle):
+    """The small-input route of cdf_cache_filter_quantize waits for its predecessors a bounded number of
+    polls. With the bound forced down to one poll a call either completes as usual or reports -1 in
+    *n_sent; it terminates either way, and with the default bound restored the same call is exact again."""
+    R, F = 40000, 64
+    cur, cached = make_pair(R, F, F, torch.float32, seed=77)
+    dcur = cur.to(DEV)
+    omask, oidx = oracle.cache_filter(to_np(cur), to_np(cached), 0.05, 0)
+    ws = ws_for(cdf, R, F)
+    rb = cdf.cdf_code_row_bytes(F, 8, 0)
+    try:
+        for limit in (1, 0):
+            cdf.cdf_set_message_wait_limit(limit)
+            for _ in range(3):
+                dcached = cached.to(DEV)
+                mask = torch.zeros(R, dtype=torch.uint8, device=DEV)
+                idx = torch.zeros(R, dtype=torch.int32, device=DEV)
+                n_sent = torch.full((1,), -7, dtype=torch.int32, device=DEV)
+                codes = torch.zeros(R * rb, dtype=torch.uint8, device=DEV)
+                meta = torch.zeros(R, 2, device=DEV)
+                cdf.cdf_cache_filter_quantize(dcur, dcached, 0.05, 0, 8, 0, 1, True, mask, idx, n_sent, codes, meta, ws)
+                torch.cuda.synchronize()
+                n = int(n_sent.item())
+                assert n == oidx.size or (limit == 1 and n == -1), n
+                np.testing.assert_array_equal(to_np(mask), omask)       # the test itself never waits
+                if n >= 0:
+                    np.testing.assert_array_equal(to_np(idx)[:n], oidx)
+                # a consumer sees "no messages" when the count is -1: nothing is applied, nothing faults
+                dst = torch.zeros(R, F, device=DEV)
+                cdf.cdf_dequantize(codes, meta, idx, n_sent, R, 8, 0, dst, True)
+                torch.cuda.synchronize()
+                if n < 0:
+                    assert int((dst != 0).sum().item()) == 0
+    finally:
+        cdf.cdf_set_message_wait_limit(0)
+
+
 @pytest.mark.parametrize("bits,qs", [(8, 0), (4, 0), (8, 1)])
 def test_subnormal_and_extreme_rows_are_bit_exact(cdf, oracle, bits, qs):
     """fp32 subnormals are not flushed and extreme ranges take the same path on both sides: rows
