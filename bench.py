@@ -425,7 +425,8 @@ def main():
     torch.cuda.empty_cache()
     sweep = None
     if not args.no_rho_sweep:
-        sweep = [{"rho": args.rho, "ms_per_step": head["ms_per_step_median"], "value": head["value_median"]}]
+        sweep = [{"rho": args.rho, "ms_per_step": head["ms_per_step_without_kernel_events"],
+                  "value": head["value_without_kernel_events"]}]   # like the other points: no per-kernel events
         for rho in (0.05, 1.0):
             m2, r2 = run_order(cdf, w, P, dev, args.order, rho, args.phi, 3, max(4, args.steps // 2), profile=False)
             sweep.append({"rho": rho, "ms_per_step": r2["ms_per_step_median"], "value": r2["value_median"]})
