@@ -454,16 +454,17 @@ __global__ __launch_bounds__(kSpmmThreads) void spmm_sliced_kernel(
 // Adds the pieces of every row that straddles chunk borders, in chunk order.
 template <typename T, int EPV>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_fixup_kernel(
-    const int* __restrict__ chunk_row, const int* __restrict__ tail_row, int64_t nchunks,
+    const int64_t* __restrict__ rowptr, const int* __restrict__ tail_row, int64_t nchunks,
     const float* __restrict__ phead, const float* __restrict__ ptail, T* __restrict__ Y, T* __restrict__ Y2,
-    int64_t ldy, int dim, int n_rows) {
+    int64_t ldy, int dim, int n_rows, int kChunk) {
   const int lane = threadIdx.x & 63;
   const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + (threadIdx.x >> 6);
   if (chunk >= nchunks) return;
   const int r = tail_row[chunk];
   if (r < 0 || r >= n_rows) return;
-  int64_t last = chunk;  // last chunk that starts inside row r
-  while (last + 1 < nchunks && chunk_row[last + 1] == r) ++last;
+  // last chunk that starts inside row r: the one that holds the row's last entry (the row runs past
+  // this chunk, so it has one). Computed, not walked: the longest rows span hundreds of chunks.
+  const int64_t last = (rowptr[r + 1] - 1) / kChunk;
   for (int col = lane * EPV; col < dim; col += 64 * EPV) {
     float acc[EPV];
 #pragma unroll
@@ -506,17 +507,16 @@ static int pick_chunk(int64_t nnz) {
 // global memory: only rows that straddle chunk borders come here).
 template <int EPV>
 __global__ __launch_bounds__(kSpmmThreads) void spmm_fixup_transform_kernel(
-    const int* __restrict__ chunk_row, const int* __restrict__ tail_row, int64_t nchunks,
+    const int64_t* __restrict__ rowptr, const int* __restrict__ tail_row, int64_t nchunks,
     const float* __restrict__ phead, const float* __restrict__ ptail, float* __restrict__ Y, int64_t ldy, int dim,
-    int n_rows, XformArgs xf) {
+    int n_rows, int kChunk, XformArgs xf) {
   extern __shared__ __align__(16) float xf_lds[];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t chunk = static_cast<int64_t>(blockIdx.x) * kSpmmWaves + wave;
   if (chunk >= nchunks) return;
   const int r = tail_row[chunk];
   if (r < 0 || r >= n_rows) return;
-  int64_t last = chunk;
-  while (last + 1 < nchunks && chunk_row[last + 1] == r) ++last;
+  const int64_t last = (rowptr[r + 1] - 1) / kChunk;
   float* rb = xf_lds + wave * xf_row_floats(dim);
   for (int col = lane * EPV; col < dim; col += 64 * EPV) {
     float acc[EPV];
@@ -634,8 +634,8 @@ static int launch_spmm(const cdf_csr* A, const T* X, int64_t ldx, T* Y, T* Y2, i
 #undef CDF_SPMM_ARGS_X
   {
     ProfScope ps(K_SPMM_FIXUP, st);
-    spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(chunk_row, tail_row, nc, phead, ptail, Y, Y2, ldy, dim,
-                                                                 A->n_rows);
+    spmm_fixup_kernel<T, EPV><<<nblocks, kSpmmThreads, 0, st>>>(A->rowptr, tail_row, nc, phead, ptail, Y, Y2, ldy, dim,
+                                                                 A->n_rows, chunk);
   }
   CDF_LAUNCH_CHECK("cdf_spmm/fixup");
   return CDF_OK;
@@ -749,8 +749,8 @@ int spmm_transform_run(const char* fn, const cdf_csr* A, const float* X, int64_t
   CDF_LAUNCH_CHECK("spmm + transform/main");
   {
     ProfScope ps(K_SPMM_FIXUP, st);
-    spmm_fixup_transform_kernel<4><<<nblocks, kSpmmThreads, lds_fix, st>>>(chunk_row, tail_row, nc, phead, ptail, M, ldm,
-                                                                           dim, A->n_rows, xf);
+    spmm_fixup_transform_kernel<4><<<nblocks, kSpmmThreads, lds_fix, st>>>(A->rowptr, tail_row, nc, phead, ptail, M, ldm,
+                                                                           dim, A->n_rows, chunk, xf);
   }
   CDF_LAUNCH_CHECK("spmm + transform/fixup");
   return CDF_OK;
