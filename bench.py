@@ -327,6 +327,9 @@ def main():
                          "auto: layers with f_out < f_in compute A (X W)")
     ap.add_argument("--no-optimised", action="store_true", help="skip the second timing in the other order")
     ap.add_argument("--no-rho-sweep", action="store_true", help="skip the timings at other send fractions")
+    ap.add_argument("--epochs", type=int, default=10,
+                    help="after the timed region: this many steps on drifting inputs from zero caches, with the cache hit "
+                         "rate and the step time of every epoch (0 to skip)")
     ap.add_argument("--graph", action="store_true",
                     help="also time the same steps replayed from captured HIP graphs (reported beside the eager figures)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -408,6 +411,20 @@ def main():
         log("[bench] timing the CPU oracle on a sample ...")
         cpu = cpu_baseline(model)
 
+    # the threshold at work: epochs on drifting inputs from zero caches (hit rate per epoch is a result here,
+    # not an input as in the stationary step above)
+    epochs = None
+    if args.epochs > 0:
+        eps_run = model.run_epochs(args.epochs)
+        for e in eps_run:
+            e["GE_per_s"] = edges / (e["ms"] * 1e-3) / 1e9
+        epochs = {"eps": w.eps, "drift": "halo rows and upstream gradients x (1 + eta_t u_r g), eta_t = 0.2 * 0.6^t, "
+                                         "u_r log-uniform in [0.1, 10] per row, g ~ N(0,1) per element; caches start at zero",
+                  "per_epoch": eps_run}
+        log("[bench] epochs from zero caches: hit rate fwd " +
+            " ".join(f"{sum(e['hit_rate_fwd']) / len(e['hit_rate_fwd']):.2f}" for e in eps_run) +
+            " | ms " + " ".join(f"{e['ms']:.1f}" for e in eps_run))
+
     # measured streaming ceiling: the library's plain copy kernel on 1 GiB (read + write bytes)
     src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
     dst = torch.zeros_like(src)
@@ -466,6 +483,7 @@ def main():
         "cpu_baseline": cpu,
         "optimised_order": optimised,
         "rho_sweep": sweep,
+        "epochs_from_zero_caches": epochs,
         "aggregation_by_position": positions,
         "kernels": kernels,
         "kernel_rooflines": per_kernel,

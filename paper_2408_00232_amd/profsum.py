@@ -24,7 +24,7 @@ COUNTER_RUNS = ["FETCH_SIZE", "WRITE_SIZE", "TCC_HIT_sum TCC_MISS_sum TCC_REQ_su
 
 def commands(workload, order, d):
     """The rocprofv3 command lines whose output this module summarises (run from the repository root)."""
-    common = f"python3 bench.py --workload {workload} --order {order} --no-cpu-baseline --no-optimised --no-rho-sweep"
+    common = f"python3 bench.py --workload {workload} --order {order} --no-cpu-baseline --no-optimised --no-rho-sweep --epochs 0"
     out = [f"rocprofv3 --kernel-trace --stats --output-format csv -d {d}/kt -o {workload} -- {common} --steps 3 --warmup 2"]
     for c in COUNTER_RUNS:
         out.append(f"rocprofv3 --pmc {c} --output-format csv -d {d}/{c.split()[0]} -o {workload} -- "

@@ -127,3 +127,52 @@ class Model:
 
     def edges_per_step(self) -> int:
         return self.nnz * len(self.layers)
+
+    def reset_caches(self) -> None:
+        """Back to the state before the first step: sender caches, the receiver's halo rows and the
+        gradient caches all zero (so the next step sends every non-zero row)."""
+        n = self.n_loc
+        for L, tf in zip(self.layers, self.tf):
+            L.cache_sent.zero_()
+            L.gcache_sent.zero_()
+            (L.tfull if tf else L.xfull)[n:].zero_()
+
+    def run_epochs(self, epochs: int, eta0: float = 0.2, kappa: float = 0.6):
+        """`epochs` steps on drifting inputs from zero caches, the threshold fixed: every epoch the
+        owners' halo rows and the upstream gradients are multiplied element-wise by 1 + eta_t u_r g
+        (g ~ N(0,1), u_r log-uniform in [0.1, 10] per row, eta_t = eta0 kappa^t), so the updates shrink
+        as they do when parameters settle and the cache hit rate rises from 0. The drift is input
+        generation (torch, outside the timed region); the step is timed with events.
+        -> [{epoch, ms, hit_rate_fwd [per layer], hit_rate_bwd [per layer]}]"""
+        import math
+        from cdfgen import rng
+        dev, h, n = self.device, self.n_halo, self.n_loc
+        self.reset_caches()
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(self.w.seed * 7919 + 1)
+        rates = []
+        for li in range(len(self.layers)):
+            lu_h = rng.uniform(self.w.seed, 500 + li, h, math.log(0.1), math.log(10.0), device=dev, dtype=torch.float64)
+            lu_n = rng.uniform(self.w.seed, 600 + li, n, math.log(0.1), math.log(10.0), device=dev, dtype=torch.float64)
+            rates.append((torch.exp(lu_h).float().view(-1, 1), torch.exp(lu_n).float().view(-1, 1)))
+        out = []
+        for t in range(epochs):
+            if t > 0:
+                eta = eta0 * kappa ** t
+                for li in range(len(self.layers)):
+                    I = self.inputs[li]
+                    for buf, rate in ((I.fresh[0], rates[li][0]), (I.dH[0], rates[li][1])):
+                        g = torch.randn(buf.shape, generator=gen, device=dev, dtype=torch.float32)
+                        g.mul_(rate * eta).add_(1.0)
+                        buf.copy_((buf.float() * g).to(buf.dtype))
+                        del g
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            a.record()
+            self._launch(0)
+            b.record()
+            torch.cuda.synchronize()
+            out.append({"epoch": t, "ms": a.elapsed_time(b),
+                        "hit_rate_fwd": [1.0 - int(L.n_sent.item()) / max(h, 1) for L in self.layers],
+                        "hit_rate_bwd": [1.0 - int(L.gn_sent.item()) / max(h, 1) for L in self.layers]})
+        return out
