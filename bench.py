@@ -278,10 +278,10 @@ def kernel_rooflines(model, w, kernels):
             per_kernel[name] = {"bound": "hbm", "algorithmic_bytes_per_launch": b, "achieved_GBps": gbs,
                                 "peak_GBps": HBM_PEAK_GBS, "frac": gbs / HBM_PEAK_GBS}
     flops = avg([2.0 * n * f * g for f, g in w.layers()])
-    # bf16-stored activations: the forward product and dM run on the bf16 matrix cores with fp32
-    # operands split into a high and a low part (2 and 3 products executed per useful one); dW, and
-    # everything of an fp32 workload, runs on the fp32 matrix cores
-    executed = {"gemm_kernel<FWD>": 2, "gemm_kernel<DM>": 3} if w.dtype == "bf16" else {}
+    # bf16-stored activations: the three products run on the bf16 matrix cores with their fp32 operands
+    # split into a high and a low part (2, 2 and 3 products executed per useful one for the forward
+    # product, dW and dM); everything of an fp32 workload runs on the fp32 matrix cores
+    executed = {"gemm_kernel<FWD>": 2, "gemm_kernel<DM>": 3, "gemm_kernel<DW>": 2} if w.dtype == "bf16" else {}
     for name in ("gemm_kernel<FWD>", "gemm_kernel<DW>", "gemm_kernel<DM>"):
         if name in kernels:
             mult = executed.get(name, 1)

@@ -363,6 +363,9 @@ int launch_dense_fwd_bf16(const void* M, int64_t ldm, const float* W, int32_t n,
 bool dense_bwd_bf16_ok(const void* M, const float* W, const float* Zs, const float* dH, int32_t f_out);
 int launch_dense_dm_bf16(const float* dH, const float* Zs, const float* W, int32_t n, int32_t f_in, int32_t f_out,
                          int relu, void* dM, int64_t lddm, hipStream_t st);
+bool dense_dw_bf16_ok(const void* M, int64_t ldm, const float* Zs, const float* dH, int32_t f_in, int32_t f_out);
+int launch_dense_dw_bf16(const void* M, int64_t ldm, const float* dH, const float* Zs, int32_t n, int32_t f_in,
+                         int32_t f_out, int relu, int slab_rows, int slabs, float* part, hipStream_t st);
 
 }  // namespace cdf
 
@@ -429,6 +432,8 @@ extern "C" int cdf_dense_bwd(const void* M, int64_t ldm, cdf_dtype dt, const flo
     a.relu = relu ? 1 : 0; a.slab_rows = slab_rows;
     const int av = vec4(M, ldm, esz), bv = vec4(dH, f_out, 4), mv = relu ? vec4(Zs, f_out, 4) : 0;
     if (dt == CDF_F32) launch_gemm<float, GEMM_DW>(a, f_in, f_out, slabs, av, bv, mv, st);
+    else if (n > 0 && dense_dw_bf16_ok(M, ldm, relu ? Zs : nullptr, dH, f_in, f_out))
+      launch_dense_dw_bf16(M, ldm, dH, relu ? Zs : nullptr, n, f_in, f_out, relu ? 1 : 0, slab_rows, slabs, part, st);
     else launch_gemm<bf16_t, GEMM_DW>(a, f_in, f_out, slabs, av, bv, mv, st);
     CDF_LAUNCH_CHECK("cdf_dense_bwd/dW");
     {

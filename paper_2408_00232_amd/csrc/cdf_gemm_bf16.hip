@@ -324,6 +324,174 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
     }
 }
 
+// ---- dW = M^T dZ for bf16-stored activations (Sec. 3.1, gradient w.r.t. the weights) ----------------
+// The reduction runs over the rows, along which neither operand is contiguous in memory, while a lane of
+// a 32x32x16 product supplies eight CONSECUTIVE reduction elements of one output row / column. The
+// tiles are therefore kept in LDS in the order they have in memory (As[row][feature], Bh / Bl
+// [row][column], a tile of 32 rows), and a lane assembles its operand from eight 16-bit LDS reads, one
+// per row: the 32 lanes of a half-wavefront read 32 neighbouring features of one row (64 contiguous
+// bytes, no bank conflict), and the row stride is chosen so that the two half-wavefronts, eight rows
+// apart, fall on different banks. M is bf16 and enters unchanged; dZ = dH * [Zs > 0] is fp32 and is
+// split into a bf16 high and low part while it is staged: dW = M^T dZh + M^T dZl, fp32 accumulation.
+// Slabs of rows, partial tiles and their ordered reduction are those of the fp32 kernel.
+constexpr int kWK = 32;            // rows (reduction elements) per LDS tile
+constexpr int kWM = 128;           // features (output rows) per block
+constexpr int kWS = 128 + 4;       // LDS row stride in bf16 elements: 66 words, so 8 rows further is 16 banks further
+
+__device__ __forceinline__ bf16x8 gather8(const uint16_t* base, int stride) {
+  // eight elements, one per LDS row, packed in ascending row order
+  u32x4 v;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    v[q] = static_cast<uint32_t>(base[(2 * q) * stride]) | (static_cast<uint32_t>(base[(2 * q + 1) * stride]) << 16);
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+template <int BN>
+__global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dw_kernel(const bf16_t* __restrict__ M, int64_t ldm,
+                                                                    const float* __restrict__ dH,
+                                                                    const float* __restrict__ Zs, int n, int f, int g,
+                                                                    int relu, int slab_rows, float* __restrict__ part) {
+  constexpr int TM = 2, TN = BN / 64;
+  constexpr int AI = kWK * (kWM / 8) / kHThreads;   // 8-feature chunks of the M tile per thread (2)
+  constexpr int BI = kWK * (BN / 4) / kHThreads;    // 4-column chunks of the dZ tile per thread (4 or 2)
+  __shared__ __attribute__((aligned(16))) uint16_t As[kWK][kWS];
+  __shared__ __attribute__((aligned(16))) uint16_t Bh[kWK][kWS];
+  __shared__ __attribute__((aligned(16))) uint16_t Bl[kWK][kWS];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, lh = lane >> 5;
+
+  // workgroup id -> (slab, tile): the tiles of one slab on ids that are equal modulo 8 (one XCD, shared L2)
+  const int tiles_m = f / kWM, tiles_n = g / BN, tiles = tiles_m * tiles_n;
+  const int group = blockIdx.x / (8 * tiles), within = blockIdx.x % (8 * tiles);
+  const int slab = group * 8 + within % 8;
+  if (static_cast<int64_t>(slab) * slab_rows >= n) return;
+  const int t = within / 8;
+  const int m0 = (t % tiles_m) * kWM, n0 = (t / tiles_m) * BN;
+  const int kbeg = slab * slab_rows, kend = min(n, kbeg + slab_rows);
+
+  u32x4 ra[AI];
+  float rb[BI][4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const int c = tid + kHThreads * i;
+      const int row = k0 + c / (kWM / 8), col = m0 + (c % (kWM / 8)) * 8;
+      if (row < kend) ra[i] = *reinterpret_cast<const u32x4*>(M + static_cast<int64_t>(row) * ldm + col);
+      else ra[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < BI; ++i) {
+      const int c = tid + kHThreads * i;
+      const int row = k0 + c / (BN / 4), col = n0 + (c % (BN / 4)) * 4;
+      if (row < kend) {
+        const int64_t off = static_cast<int64_t>(row) * g + col;
+        const float4 v = *reinterpret_cast<const float4*>(dH + off);
+        rb[i][0] = v.x; rb[i][1] = v.y; rb[i][2] = v.z; rb[i][3] = v.w;
+        if (relu) {
+          const float4 z = *reinterpret_cast<const float4*>(Zs + off);
+          rb[i][0] = z.x > 0.0f ? rb[i][0] : 0.0f;
+          rb[i][1] = z.y > 0.0f ? rb[i][1] : 0.0f;
+          rb[i][2] = z.z > 0.0f ? rb[i][2] : 0.0f;
+          rb[i][3] = z.w > 0.0f ? rb[i][3] : 0.0f;
+        }
+      } else {
+        rb[i][0] = rb[i][1] = rb[i][2] = rb[i][3] = 0.0f;
+      }
+    }
+  };
+  auto stage = [&]() {
+#pragma unroll
+    for (int i = 0; i < AI; ++i) {
+      const int c = tid + kHThreads * i;
+      uint2* dst = reinterpret_cast<uint2*>(&As[c / (kWM / 8)][(c % (kWM / 8)) * 8]);   // rows are 8-byte aligned
+      dst[0] = make_uint2(ra[i][0], ra[i][1]);
+      dst[1] = make_uint2(ra[i][2], ra[i][3]);
+    }
+#pragma unroll
+    for (int i = 0; i < BI; ++i) {
+      const int c = tid + kHThreads * i;
+      uint16_t hi[4], lo[4];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) split_bf16(rb[i][j], hi[j], lo[j]);
+      const int r = c / (BN / 4), col = (c % (BN / 4)) * 4;
+      *reinterpret_cast<uint2*>(&Bh[r][col]) = make_uint2(hi[0] | (static_cast<uint32_t>(hi[1]) << 16),
+                                                         hi[2] | (static_cast<uint32_t>(hi[3]) << 16));
+      *reinterpret_cast<uint2*>(&Bl[r][col]) = make_uint2(lo[0] | (static_cast<uint32_t>(lo[1]) << 16),
+                                                         lo[2] | (static_cast<uint32_t>(lo[3]) << 16));
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+  fetch(kbeg);
+  for (int k0 = kbeg; k0 < kend; k0 += kWK) {
+    stage();
+    __syncthreads();
+    if (k0 + kWK < kend) fetch(k0 + kWK);
+#pragma unroll
+    for (int ks = 0; ks < kWK; ks += 16) {
+      // lane (l32, lh): output row / column l32 of its 32x32 tile, reduction rows ks + lh*8 .. + 7
+      bf16x8 a[TM], bh[TN], bl[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) a[i] = gather8(&As[ks + lh * 8][wm * 64 + i * 32 + l32], kWS);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        bh[j] = gather8(&Bh[ks + lh * 8][wn * (BN / 2) + j * 32 + l32], kWS);
+        bl[j] = gather8(&Bl[ks + lh * 8][wn * (BN / 2) + j * 32 + l32], kWS);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bl[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], bh[j], acc[i][j], 0, 0, 0);
+        }
+    }
+    __syncthreads();
+  }
+
+  // lane holds column l32 and rows (e/4)*8 + lh*4 + e%4 of each 32x32 tile; every tile is full
+  float* out = part + static_cast<int64_t>(slab) * f * g;
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * (BN / 2) + j * 32 + l32;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int row = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+        out[static_cast<int64_t>(row) * g + col] = acc[i][j][e];
+      }
+    }
+}
+
+// The bf16 matrix-core dW kernel takes whole tiles only: 128 features x 64 or 128 columns, 16-byte
+// aligned rows of M, dH and Zs.
+bool dense_dw_bf16_ok(const void* M, int64_t ldm, const float* Zs, const float* dH, int32_t f_in, int32_t f_out) {
+  return f_in % kWM == 0 && f_out % 64 == 0 && ldm % 8 == 0 && aligned(M, 16) && aligned(dH, 16) &&
+         (!Zs || aligned(Zs, 16));
+}
+
+int launch_dense_dw_bf16(const void* M, int64_t ldm, const float* dH, const float* Zs, int32_t n, int32_t f_in,
+                         int32_t f_out, int relu, int slab_rows, int slabs, float* part, hipStream_t st) {
+  ProfScope ps(K_GEMM_DW, st);
+  const bf16_t* m = static_cast<const bf16_t*>(M);
+  const int bn = f_out % 128 == 0 ? 128 : 64;
+  const int tiles = (f_in / kWM) * (f_out / bn);
+  const unsigned grid = static_cast<unsigned>(ceil_div(slabs, 8) * 8 * tiles);
+  if (bn == 128) gemm_bf16_dw_kernel<128><<<grid, kHThreads, 0, st>>>(m, ldm, dH, Zs, n, f_in, f_out, relu, slab_rows, part);
+  else gemm_bf16_dw_kernel<64><<<grid, kHThreads, 0, st>>>(m, ldm, dH, Zs, n, f_in, f_out, relu, slab_rows, part);
+  return CDF_OK;
+}
+
 bool dense_bwd_bf16_ok(const void* M, const float* W, const float* Zs, const float* dH, int32_t f_out) {
   return f_out % 8 == 0 && aligned(W, 16) && aligned(dH, 16) && (!Zs || aligned(Zs, 16)) && aligned(M, 2);
 }
