@@ -268,9 +268,10 @@ int cdf_dense_fwd(const void* M, int64_t ldm, cdf_dtype dt, const float* W, int3
  *   dZ = relu ? dH * [Zs > 0] : dH      (Zs: Z or H of the forward pass - same sign test)
  *   dW [f_in x f_out] fp32 = M^T dZ     (row blocks reduced in a fixed order: reproducible)
  *   dM [n x f_in] type dt  = dZ W^T     (skipped when dM is NULL)
- * fp32 matrix instructions, except dM of bf16 activations when f_out % 8 == 0 and W, dH, Zs are
- * 16-byte aligned: bf16 matrix instructions on dZ and W each split into a bf16 high and low part
- * (three products, the low x low one dropped), fp32 accumulation, bf16 result.
+ * fp32 matrix instructions, except for bf16 activations with 16-byte aligned W, dH, Zs: dM (f_out % 8
+ * == 0) on the bf16 matrix instructions with dZ and W each split into a bf16 high and low part (three
+ * products, the low x low one dropped), fp32 accumulation, bf16 result; dW (f_in % 128 == 0, f_out %
+ * 64 == 0, 16-byte aligned rows of M) likewise with dZ split in two (M is bf16 already).
  */
 int cdf_dense_bwd(const void* M, int64_t ldm, cdf_dtype dt, const float* W, const float* Zs,
                   const float* dH, int32_t n, int32_t f_in, int32_t f_out, int relu, float* dW,

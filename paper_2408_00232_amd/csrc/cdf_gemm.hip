@@ -421,9 +421,8 @@ extern "C" int cdf_dense_bwd(const void* M, int64_t ldm, cdf_dtype dt, const flo
     CDF_FAIL(CDF_ERR_WORKSPACE, "cdf_dense_bwd: workspace too small (%zu < %zu)", ws_bytes, need);
   float* part = static_cast<float*>(ws);
   const int64_t count = static_cast<int64_t>(f_in) * f_out;
-  // bf16-stored activations: dM on the bf16 matrix cores (fp32 operands split in two). dW stays on the
-  // fp32 cores: its reduction runs over the rows, along which no operand is contiguous, and a bf16
-  // version that gathered its operands with narrow loads measured slower (4.8 against 2.7 ms).
+  // bf16-stored activations: dM and (for whole 128 x 64 tiles) dW on the bf16 matrix cores, fp32 operands
+  // split into a bf16 high and low part
   const bool bf16_cores = dt == CDF_BF16 && n > 0 && dense_bwd_bf16_ok(M, W, relu ? Zs : nullptr, dH, f_out);
   // dW = M^T dZ
   {

@@ -4,10 +4,11 @@
 // Z = M hi + M lo with fp32 accumulation inside v_mfma_f32_32x32x16_bf16 - two bf16 products at
 // sixteen times the fp32 matrix rate in place of one fp32 product.
 //
-// Tile: 128 x BN outputs (BN = 128 or 64) per block of four wavefronts (2 x 2), reduction in steps of 32.
-// LDS holds the operands k-contiguous per row (As[m][k], Bh[n][k], Bl[n][k]) so that a lane reads
-// its eight consecutive k values of a 32x32x16 operand with one 16-byte access. The next k-tile
-// is fetched into registers while the current one is multiplied.
+// Tile: 128 x BN outputs (BN = 128 or 64) per block of four wavefronts (2 x 2), 256 x 128 on large inputs,
+// reduction in steps of 32. LDS holds the operands k-contiguous per row (As[m][k], Bh[n][k], Bl[n][k]) so
+// that a lane reads its eight consecutive k values of a 32x32x16 operand with one 16-byte access. The next
+// k-tile is fetched into registers while the current one is multiplied. The column blocks of a row tile
+// run on one XCD at the same time (1-D grid, see xcd_tile), so the row tile's operand comes from memory once.
 #include "cdf_common.h"
 
 namespace cdf {
@@ -16,7 +17,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kHM = 128;      // output rows per block
 constexpr int kHK = 32;       // reduction elements per LDS tile
 constexpr int kHS = kHK + 8;  // LDS row stride in bf16 elements (80 bytes: 16-byte aligned rows)
 constexpr int kHThreads = 256;
@@ -56,29 +56,51 @@ __global__ __launch_bounds__(256) void split_transpose_kernel(const float* __res
 
 // PRE: Wh / Wl hold the split, transposed weight (see above) and W is unused; otherwise every block
 // splits its own part of W while staging it.
-template <int BN, bool PRE>
+// Output tile of a workgroup in a 1-D grid of 8 * ceil(row_tiles / 8) * col_blocks workgroups. Workgroups are
+// handed to the 8 XCDs in turn, so workgroup b runs on XCD b mod 8; the column blocks of one row tile get
+// consecutive slots of ONE XCD, run there at the same time and read the row tile's operand once into that
+// XCD's L2 instead of once per column block from memory. False for the padding of the last group of 8.
+__device__ __forceinline__ bool xcd_tile(int row_tiles, int col_blocks, int& row_tile, int& col_block) {
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  col_block = slot % col_blocks;
+  row_tile = (slot / col_blocks) * 8 + xcd;
+  return row_tile < row_tiles;
+}
+static unsigned xcd_grid(int64_t row_tiles, int64_t col_blocks) {
+  return static_cast<unsigned>(ceil_div(row_tiles, 8) * 8 * col_blocks);
+}
+
+template <int BN, bool PRE, int TM>
 __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_t* __restrict__ M, int64_t ldm,
                                                                      const float* __restrict__ W,
                                                                      const uint16_t* __restrict__ Wh,
                                                                      const uint16_t* __restrict__ Wl, int n, int f, int g,
                                                                      int relu, float* __restrict__ Z,
                                                                      float* __restrict__ H) {
-  constexpr int TM = 2, TN = BN / 64;
+  constexpr int TN = BN / 64;
+  constexpr int HM = 64 * TM;                     // output rows per block (two wavefronts of TM tiles of 32)
   constexpr int BI = BN * (kHK / 8) / kHThreads;  // (column, k-block) items of the W tile per thread
-  __shared__ __attribute__((aligned(16))) uint16_t As[kHM][kHS];
+  __shared__ __attribute__((aligned(16))) uint16_t As[HM][kHS];
   __shared__ __attribute__((aligned(16))) uint16_t Bh[BN][kHS];
   __shared__ __attribute__((aligned(16))) uint16_t Bl[BN][kHS];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, lh = lane >> 5;
-  const int m0 = blockIdx.x * kHM, n0 = blockIdx.y * BN;
+  int row_tile, col_block;
+  if (!xcd_tile((n + HM - 1) / HM, (g + BN - 1) / BN, row_tile, col_block)) return;
+  const int m0 = row_tile * HM, n0 = col_block * BN;
 
-  constexpr int AI = kHM * (kHK / 8) / kHThreads;   // 8-element chunks of the M tile per thread
+  constexpr int AI = HM * (kHK / 8) / kHThreads;   // 8-element chunks of the M tile per thread
   u32x4 ra[AI];
   float rb[PRE ? 1 : BI][8];    // BI items of 8 consecutive k for one output column (fp32, to be split)
   u32x4 rh[PRE ? BI : 1], rl[PRE ? BI : 1];   // the same items, already split
 
+  // item -> (column, block of 8 k) of the W tile. Split W is stored transposed, a column's k run is contiguous:
+  // neighbouring lanes take neighbouring k blocks of one column (whole 64-byte runs). Unsplit W is row-major
+  // [k][column]: neighbouring lanes take neighbouring columns.
+  auto b_col = [](int item) { return PRE ? item / (kHK / 8) : item % BN; };
+  auto b_kb = [](int item) { return PRE ? item % (kHK / 8) : item / BN; };
   auto fetch = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
@@ -90,7 +112,7 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
       const int item = tid + kHThreads * i;
-      const int col = n0 + item % BN, kb = k0 + (item / BN) * 8;
+      const int col = n0 + b_col(item), kb = k0 + b_kb(item) * 8;
       if (PRE) {
         if (col < g && kb < f) {
           rh[i] = *reinterpret_cast<const u32x4*>(Wh + static_cast<int64_t>(col) * f + kb);
@@ -115,8 +137,8 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
     for (int i = 0; i < BI; ++i) {
       const int item = tid + kHThreads * i;
       if (PRE) {
-        *reinterpret_cast<u32x4*>(&Bh[item % BN][(item / BN) * 8]) = rh[i];
-        *reinterpret_cast<u32x4*>(&Bl[item % BN][(item / BN) * 8]) = rl[i];
+        *reinterpret_cast<u32x4*>(&Bh[b_col(item)][b_kb(item) * 8]) = rh[i];
+        *reinterpret_cast<u32x4*>(&Bl[b_col(item)][b_kb(item) * 8]) = rl[i];
         continue;
       }
       uint16_t hi[8], lo[8];
@@ -152,7 +174,7 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
       bf16x8 a[TM], bh[TN], bl[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i)
-        a[i] = *reinterpret_cast<const bf16x8*>(&As[wm * 64 + i * 32 + l32][ks + lh * 8]);
+        a[i] = *reinterpret_cast<const bf16x8*>(&As[wm * (HM / 2) + i * 32 + l32][ks + lh * 8]);
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
         bh[j] = *reinterpret_cast<const bf16x8*>(&Bh[wn * (BN / 2) + j * 32 + l32][ks + lh * 8]);
@@ -178,7 +200,7 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
       if (col >= g) continue;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+        const int row = m0 + wm * (HM / 2) + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
         if (row >= n) continue;
         const float v = acc[i][j][e];
         const int64_t off = static_cast<int64_t>(row) * g + col;
@@ -193,22 +215,25 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
 // features), so each is split into bf16 high / low parts while it is staged:
 //   dM = dZh Wh^T + dZh Wl^T + dZl Wh^T          (the low x low term is below 2^-16 of the result)
 // The result is stored as bf16, which is the type the aggregation that follows reads.
-template <int BN>
+template <int BN, int TM>
 __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float* __restrict__ dH,
                                                                     const float* __restrict__ Zs,
                                                                     const float* __restrict__ W, int n, int f, int g,
                                                                     int relu, bf16_t* __restrict__ dM, int64_t ldo) {
-  constexpr int TM = 2, TN = BN / 64;
-  constexpr int AI = kHM * (kHK / 8) / kHThreads;
+  constexpr int TN = BN / 64;
+  constexpr int HM = 64 * TM;
+  constexpr int AI = HM * (kHK / 8) / kHThreads;
   constexpr int BI = BN * (kHK / 8) / kHThreads;
-  __shared__ __attribute__((aligned(16))) uint16_t Ah[kHM][kHS];
-  __shared__ __attribute__((aligned(16))) uint16_t Al[kHM][kHS];
+  __shared__ __attribute__((aligned(16))) uint16_t Ah[HM][kHS];
+  __shared__ __attribute__((aligned(16))) uint16_t Al[HM][kHS];
   __shared__ __attribute__((aligned(16))) uint16_t Bh[BN][kHS];
   __shared__ __attribute__((aligned(16))) uint16_t Bl[BN][kHS];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, lh = lane >> 5;
-  const int m0 = blockIdx.x * kHM, n0 = blockIdx.y * BN;
+  int row_tile, col_block;
+  if (!xcd_tile((n + HM - 1) / HM, (f + BN - 1) / BN, row_tile, col_block)) return;
+  const int m0 = row_tile * HM, n0 = col_block * BN;
 
   float ra[AI][8], rb[BI][8];
   auto load8 = [](const float* p, float (&v)[8]) {
@@ -289,8 +314,8 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
       bf16x8 ah[TM], al[TM], bh[TN], bl[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
-        ah[i] = *reinterpret_cast<const bf16x8*>(&Ah[wm * 64 + i * 32 + l32][ks + lh * 8]);
-        al[i] = *reinterpret_cast<const bf16x8*>(&Al[wm * 64 + i * 32 + l32][ks + lh * 8]);
+        ah[i] = *reinterpret_cast<const bf16x8*>(&Ah[wm * (HM / 2) + i * 32 + l32][ks + lh * 8]);
+        al[i] = *reinterpret_cast<const bf16x8*>(&Al[wm * (HM / 2) + i * 32 + l32][ks + lh * 8]);
       }
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
@@ -316,7 +341,7 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
       if (col >= f) continue;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+        const int row = m0 + wm * (HM / 2) + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
         if (row >= n) continue;
         float one[1] = {acc[i][j][e]};
         VecIO<bf16_t, 1>::store(dM + static_cast<int64_t>(row) * ldo + col, one);
@@ -492,6 +517,11 @@ int launch_dense_dw_bf16(const void* M, int64_t ldm, const float* dH, const floa
   return CDF_OK;
 }
 
+// Rows from which the forward and dM products take 256-row tiles (a wavefront then holds 4 x 2 tiles of
+// 32 x 32 and reads 0.5 instead of 0.75 LDS operands per matrix instruction): enough row tiles to fill
+// the chip's 512 workgroup slots at two column blocks.
+constexpr int kTallRows = 256 * 512;
+
 bool dense_bwd_bf16_ok(const void* M, const float* W, const float* Zs, const float* dH, int32_t f_out) {
   return f_out % 8 == 0 && aligned(W, 16) && aligned(dH, 16) && (!Zs || aligned(Zs, 16)) && aligned(M, 2);
 }
@@ -500,10 +530,12 @@ int launch_dense_dm_bf16(const float* dH, const float* Zs, const float* W, int32
                          int relu, void* dM, int64_t lddm, hipStream_t st) {
   ProfScope ps(K_GEMM_DM, st);
   const int bn = f_in > 64 ? 128 : 64;
-  const dim3 grid(static_cast<unsigned>(ceil_div(n, kHM)), static_cast<unsigned>(ceil_div(f_in, bn)));
+  const bool tall = bn == 128 && n >= kTallRows;
+  const unsigned grid = xcd_grid(ceil_div(n, tall ? 256 : 128), ceil_div(f_in, bn));
   bf16_t* o = static_cast<bf16_t*>(dM);
-  if (bn == 128) gemm_bf16_dm_kernel<128><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
-  else gemm_bf16_dm_kernel<64><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
+  if (tall) gemm_bf16_dm_kernel<128, 4><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
+  else if (bn == 128) gemm_bf16_dm_kernel<128, 2><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
+  else gemm_bf16_dm_kernel<64, 2><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
   return CDF_OK;
 }
 
@@ -523,7 +555,8 @@ int launch_dense_fwd_bf16(const void* M, int64_t ldm, const float* W, int32_t n,
   // 128 columns per block at most: the wider tile measured slower (three resident blocks per compute
   // unit hide the barrier and LDS latency of this short pipeline better than one wide block)
   const int bn = f_out > 64 ? 128 : 64;
-  const dim3 grid(static_cast<unsigned>(ceil_div(n, kHM)), static_cast<unsigned>(ceil_div(f_out, bn)));
+  const bool tall = bn == 128 && n >= kTallRows;
+  const unsigned grid = xcd_grid(ceil_div(n, tall ? 256 : 128), ceil_div(f_out, bn));
   const bool pre = ws && aligned(ws, 256) && ws_bytes >= dense_fwd_bf16_workspace_bytes(f_in, f_out);
   uint16_t* wh = static_cast<uint16_t*>(ws);
   uint16_t* wl = pre ? wh + align_up(static_cast<size_t>(f_in) * f_out * 2, 256) / 2 : nullptr;
@@ -532,11 +565,12 @@ int launch_dense_fwd_bf16(const void* M, int64_t ldm, const float* W, int32_t n,
     const dim3 sg(static_cast<unsigned>(ceil_div(f_in, 32)), static_cast<unsigned>(ceil_div(f_out, 32)));
     split_transpose_kernel<<<sg, 256, 0, st>>>(W, f_in, f_out, wh, wl);
   }
-#define CDF_BF16_FWD(BNV)                                                                                            \
-  if (pre) gemm_bf16_fwd_kernel<BNV, true><<<grid, kHThreads, 0, st>>>(m, ldm, W, wh, wl, n, f_in, f_out, relu, Z, H); \
-  else gemm_bf16_fwd_kernel<BNV, false><<<grid, kHThreads, 0, st>>>(m, ldm, W, nullptr, nullptr, n, f_in, f_out, relu, Z, H)
-  if (bn == 128) { CDF_BF16_FWD(128); }
-  else { CDF_BF16_FWD(64); }
+#define CDF_BF16_FWD(BNV, TMV)                                                                                            \
+  if (pre) gemm_bf16_fwd_kernel<BNV, true, TMV><<<grid, kHThreads, 0, st>>>(m, ldm, W, wh, wl, n, f_in, f_out, relu, Z, H); \
+  else gemm_bf16_fwd_kernel<BNV, false, TMV><<<grid, kHThreads, 0, st>>>(m, ldm, W, nullptr, nullptr, n, f_in, f_out, relu, Z, H)
+  if (tall) { CDF_BF16_FWD(128, 4); }
+  else if (bn == 128) { CDF_BF16_FWD(128, 2); }
+  else { CDF_BF16_FWD(64, 2); }
 #undef CDF_BF16_FWD
   return CDF_OK;
 }

@@ -511,6 +511,32 @@ def test_dense_fwd_bwd(cdf, oracle, n, f, g, relu, dtype):
         assert_bf16_close(to_np(dM), odM, "dM")
 
 
+@pytest.mark.parametrize("n,f,g", [(131072 + 77, 256, 192), (131072, 128, 128)])
+def test_dense_bf16_tall_tiles(cdf, oracle, n, f, g):
+    """bf16 activations on inputs of 131072 rows and more: the forward and dM products take 256-row
+    tiles there (a ragged last row tile and a half-filled last column block in the first shape)."""
+    M = features.normal_matrix(17, n + f, n, f).to(torch.bfloat16)
+    W = features.glorot(17, g, f, g)
+    dH = features.normal_matrix(18, n + g, n, g)
+    M_, dH_, W_ = M.to(DEV), dH.to(DEV), W.to(DEV)
+    Z = torch.zeros(n, g, device=DEV)
+    H = torch.zeros(n, g, device=DEV)
+    ws = ws_for(cdf, n, max(f, g))
+    cdf.cdf_dense_fwd(M_, W_, True, Z, H)
+    torch.cuda.synchronize()
+    oZ, oH = oracle.dense_fwd(to_np(M), W.numpy(), True)
+    assert_rows_close(to_np(Z), oZ, what="Z")
+    assert_rows_close(to_np(H), oH, rel=1e-4, frob=1e-5, what="H")
+    Zs = torch.from_numpy(oZ).to(DEV)
+    dW = torch.zeros(f, g, device=DEV)
+    dM = torch.zeros(n, f, dtype=torch.bfloat16, device=DEV)
+    cdf.cdf_dense_bwd(M_, W_, Zs, dH_, True, dW, dM, ws)
+    torch.cuda.synchronize()
+    odW, odM = oracle.dense_bwd(to_np(M), W.numpy(), oZ, dH.numpy(), True)
+    assert_rows_close(to_np(dW), odW, what="dW")
+    assert_bf16_close(to_np(dM), odM, "dM")
+
+
 def lockstep_messages(oracle, rows, cache0, L, h, eps, norm, bits, qs, commit, delta):
     """The cache test and the message build of a backward step, redone by the oracle on the halo gradient
     rows the GPU step itself produced (`rows`) against the cache the step started from (`cache0`): mask,
