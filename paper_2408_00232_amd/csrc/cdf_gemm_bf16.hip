@@ -4,8 +4,7 @@
 // Z = M hi + M lo with fp32 accumulation inside v_mfma_f32_32x32x16_bf16 - two bf16 products at
 // sixteen times the fp32 matrix rate in place of one fp32 product.
 //
-// Tile: 128 x BN outputs (BN = 128 or 64) per block of four wavefronts (2 x 2), 256 x 128 on large inputs,
-// reduction in steps of 32. LDS holds the operands k-contiguous per row (As[m][k], Bh[n][k], Bl[n][k]) so
+// Tile: 128 x BN outputs (BN = 128 or 64) per block of four wavefronts (2 x 2), reduction in steps of 32. LDS holds the operands k-contiguous per row (As[m][k], Bh[n][k], Bl[n][k]) so
 // that a lane reads its eight consecutive k values of a 32x32x16 operand with one 16-byte access. The next
 // k-tile is fetched into registers while the current one is multiplied. The column blocks of a row tile
 // run on one XCD at the same time (1-D grid, see xcd_tile), so the row tile's operand comes from memory once.
@@ -70,14 +69,14 @@ static unsigned xcd_grid(int64_t row_tiles, int64_t col_blocks) {
   return static_cast<unsigned>(ceil_div(row_tiles, 8) * 8 * col_blocks);
 }
 
-template <int BN, bool PRE, int TM>
+template <int BN, bool PRE>
 __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_t* __restrict__ M, int64_t ldm,
                                                                      const float* __restrict__ W,
                                                                      const uint16_t* __restrict__ Wh,
                                                                      const uint16_t* __restrict__ Wl, int n, int f, int g,
                                                                      int relu, float* __restrict__ Z,
                                                                      float* __restrict__ H) {
-  constexpr int TN = BN / 64;
+  constexpr int TM = 2, TN = BN / 64;
   constexpr int HM = 64 * TM;                     // output rows per block (two wavefronts of TM tiles of 32)
   constexpr int BI = BN * (kHK / 8) / kHThreads;  // (column, k-block) items of the W tile per thread
   __shared__ __attribute__((aligned(16))) uint16_t As[HM][kHS];
@@ -101,57 +100,57 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
   // [k][column]: neighbouring lanes take neighbouring columns.
   auto b_col = [](int item) { return PRE ? item / (kHK / 8) : item % BN; };
   auto b_kb = [](int item) { return PRE ? item % (kHK / 8) : item / BN; };
+  // Loads carry no branches and nothing waits for them before the products of the current tile have been
+  // issued: addresses are clamped into the operand (rows past n and columns past g feed outputs that are never
+  // stored; k blocks past f are zeroed when they are staged, on both operands).
   auto fetch = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
       const int c = tid + kHThreads * i;
-      const int row = m0 + c / (kHK / 8), k = k0 + (c % (kHK / 8)) * 8;
-      if (row < n && k < f) ra[i] = *reinterpret_cast<const u32x4*>(M + static_cast<int64_t>(row) * ldm + k);
-      else ra[i] = u32x4{0u, 0u, 0u, 0u};
+      const int row = min(m0 + c / (kHK / 8), n - 1), k = min(k0 + (c % (kHK / 8)) * 8, f - 8);
+      ra[i] = *reinterpret_cast<const u32x4*>(M + static_cast<int64_t>(row) * ldm + k);
     }
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
       const int item = tid + kHThreads * i;
-      const int col = n0 + b_col(item), kb = k0 + b_kb(item) * 8;
+      const int col = min(n0 + b_col(item), g - 1), kb = min(k0 + b_kb(item) * 8, f - 8);
       if (PRE) {
-        if (col < g && kb < f) {
-          rh[i] = *reinterpret_cast<const u32x4*>(Wh + static_cast<int64_t>(col) * f + kb);
-          rl[i] = *reinterpret_cast<const u32x4*>(Wl + static_cast<int64_t>(col) * f + kb);
-        } else {
-          rh[i] = rl[i] = u32x4{0u, 0u, 0u, 0u};
-        }
+        rh[i] = *reinterpret_cast<const u32x4*>(Wh + static_cast<int64_t>(col) * f + kb);
+        rl[i] = *reinterpret_cast<const u32x4*>(Wl + static_cast<int64_t>(col) * f + kb);
       } else {
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          rb[i][j] = (col < g && kb + j < f) ? W[static_cast<int64_t>(kb + j) * g + col] : 0.0f;
+        for (int j = 0; j < 8; ++j) rb[i][j] = W[static_cast<int64_t>(kb + j) * g + col];
       }
     }
   };
-  auto stage = [&]() {
+  const u32x4 zero4 = {0u, 0u, 0u, 0u};
+  auto stage = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
       const int c = tid + kHThreads * i;
-      *reinterpret_cast<u32x4*>(&As[c / (kHK / 8)][(c % (kHK / 8)) * 8]) = ra[i];
+      const bool kin = k0 + (c % (kHK / 8)) * 8 < f;
+      *reinterpret_cast<u32x4*>(&As[c / (kHK / 8)][(c % (kHK / 8)) * 8]) = kin ? ra[i] : zero4;
     }
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
       const int item = tid + kHThreads * i;
+      const bool kin = k0 + b_kb(item) * 8 < f;
       if (PRE) {
-        *reinterpret_cast<u32x4*>(&Bh[b_col(item)][b_kb(item) * 8]) = rh[i];
-        *reinterpret_cast<u32x4*>(&Bl[b_col(item)][b_kb(item) * 8]) = rl[i];
+        *reinterpret_cast<u32x4*>(&Bh[b_col(item)][b_kb(item) * 8]) = kin ? rh[i] : zero4;
+        *reinterpret_cast<u32x4*>(&Bl[b_col(item)][b_kb(item) * 8]) = kin ? rl[i] : zero4;
         continue;
       }
       uint16_t hi[8], lo[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) split_bf16(rb[i][j], hi[j], lo[j]);
+      for (int j = 0; j < 8; ++j) split_bf16(kin ? rb[i][j] : 0.0f, hi[j], lo[j]);
       u32x4 ph, pl;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
         ph[q] = static_cast<uint32_t>(hi[2 * q]) | (static_cast<uint32_t>(hi[2 * q + 1]) << 16);
         pl[q] = static_cast<uint32_t>(lo[2 * q]) | (static_cast<uint32_t>(lo[2 * q + 1]) << 16);
       }
-      *reinterpret_cast<u32x4*>(&Bh[item % BN][(item / BN) * 8]) = ph;
-      *reinterpret_cast<u32x4*>(&Bl[item % BN][(item / BN) * 8]) = pl;
+      *reinterpret_cast<u32x4*>(&Bh[b_col(item)][b_kb(item) * 8]) = ph;
+      *reinterpret_cast<u32x4*>(&Bl[b_col(item)][b_kb(item) * 8]) = pl;
     }
   };
 
@@ -165,7 +164,7 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
 
   fetch(0);
   for (int k0 = 0; k0 < f; k0 += kHK) {
-    stage();
+    stage(k0);
     __syncthreads();
     if (k0 + kHK < f) fetch(k0 + kHK);
 #pragma unroll
@@ -215,12 +214,12 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
 // features), so each is split into bf16 high / low parts while it is staged:
 //   dM = dZh Wh^T + dZh Wl^T + dZl Wh^T          (the low x low term is below 2^-16 of the result)
 // The result is stored as bf16, which is the type the aggregation that follows reads.
-template <int BN, int TM>
+template <int BN, bool RELU>
 __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float* __restrict__ dH,
                                                                     const float* __restrict__ Zs,
                                                                     const float* __restrict__ W, int n, int f, int g,
-                                                                    int relu, bf16_t* __restrict__ dM, int64_t ldo) {
-  constexpr int TN = BN / 64;
+                                                                    bf16_t* __restrict__ dM, int64_t ldo) {
+  constexpr int TM = 2, TN = BN / 64;
   constexpr int HM = 64 * TM;
   constexpr int AI = HM * (kHK / 8) / kHThreads;
   constexpr int BI = BN * (kHK / 8) / kHThreads;
@@ -235,40 +234,32 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
   if (!xcd_tile((n + HM - 1) / HM, (f + BN - 1) / BN, row_tile, col_block)) return;
   const int m0 = row_tile * HM, n0 = col_block * BN;
 
-  float ra[AI][8], rb[BI][8];
+  float ra[AI][8], rz[RELU ? AI : 1][8], rb[BI][8];
   auto load8 = [](const float* p, float (&v)[8]) {
     const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
   };
+  // Branch-free loads with clamped addresses; the ReLU mask, the zeroing of k blocks past g and the split are
+  // applied when the tile is staged, so that nothing waits for a load before the current tile's products.
+  // addresses: a tile base that is the same for the whole block plus 32-bit element offsets
+  const float* dHt = dH + static_cast<int64_t>(m0) * g;
+  const float* Zt = RELU ? Zs + static_cast<int64_t>(m0) * g : nullptr;
+  const float* Wt = W + static_cast<int64_t>(n0) * g;
+  const int kk = (tid % (kHK / 8)) * 8;   // the thread's k block inside a tile, the same for all its items
+  uint32_t arow[AI], brow[BI];
+#pragma unroll
+  for (int i = 0; i < AI; ++i) arow[i] = static_cast<uint32_t>(min((tid + kHThreads * i) / (kHK / 8), n - 1 - m0)) * g;
+#pragma unroll
+  for (int i = 0; i < BI; ++i) brow[i] = static_cast<uint32_t>(min((tid + kHThreads * i) / (kHK / 8), f - 1 - n0)) * g;
   auto fetch = [&](int k0) {
+    const uint32_t k = min(k0 + kk, g - 8);
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
-      const int c = tid + kHThreads * i;
-      const int row = m0 + c / (kHK / 8), k = k0 + (c % (kHK / 8)) * 8;
-      if (row < n && k < g) {
-        load8(dH + static_cast<int64_t>(row) * g + k, ra[i]);
-        if (relu) {
-          float z[8];
-          load8(Zs + static_cast<int64_t>(row) * g + k, z);
-#pragma unroll
-          for (int j = 0; j < 8; ++j) ra[i][j] = z[j] > 0.0f ? ra[i][j] : 0.0f;
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) ra[i][j] = 0.0f;
-      }
+      load8(dHt + (arow[i] + k), ra[i]);
+      if (RELU) load8(Zt + (arow[i] + k), rz[i]);
     }
 #pragma unroll
-    for (int i = 0; i < BI; ++i) {
-      const int item = tid + kHThreads * i;
-      const int col = n0 + item / (kHK / 8), k = k0 + (item % (kHK / 8)) * 8;
-      if (col < f && k < g) {
-        load8(W + static_cast<int64_t>(col) * g + k, rb[i]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) rb[i][j] = 0.0f;
-      }
-    }
+    for (int i = 0; i < BI; ++i) load8(Wt + (brow[i] + k), rb[i]);
   };
   auto put = [](const float (&v)[8], uint16_t* hi_dst, uint16_t* lo_dst) {
     uint16_t hi[8], lo[8];
@@ -283,16 +274,24 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
     *reinterpret_cast<u32x4*>(hi_dst) = ph;
     *reinterpret_cast<u32x4*>(lo_dst) = pl;
   };
-  auto stage = [&]() {
+  auto stage = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
       const int c = tid + kHThreads * i;
-      put(ra[i], &Ah[c / (kHK / 8)][(c % (kHK / 8)) * 8], &Al[c / (kHK / 8)][(c % (kHK / 8)) * 8]);
+      const bool kin = k0 + (c % (kHK / 8)) * 8 < g;
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = (kin && (!RELU || rz[RELU ? i : 0][j] > 0.0f)) ? ra[i][j] : 0.0f;
+      put(v, &Ah[c / (kHK / 8)][(c % (kHK / 8)) * 8], &Al[c / (kHK / 8)][(c % (kHK / 8)) * 8]);
     }
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
       const int item = tid + kHThreads * i;
-      put(rb[i], &Bh[item / (kHK / 8)][(item % (kHK / 8)) * 8], &Bl[item / (kHK / 8)][(item % (kHK / 8)) * 8]);
+      const bool kin = k0 + (item % (kHK / 8)) * 8 < g;
+      float v[8];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) v[j] = kin ? rb[i][j] : 0.0f;
+      put(v, &Bh[item / (kHK / 8)][(item % (kHK / 8)) * 8], &Bl[item / (kHK / 8)][(item % (kHK / 8)) * 8]);
     }
   };
 
@@ -306,7 +305,7 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
 
   fetch(0);
   for (int k0 = 0; k0 < g; k0 += kHK) {
-    stage();
+    stage(k0);
     __syncthreads();
     if (k0 + kHK < g) fetch(k0 + kHK);
 #pragma unroll
@@ -372,11 +371,11 @@ __device__ __forceinline__ bf16x8 gather8(const uint16_t* base, int stride) {
   return __builtin_bit_cast(bf16x8, v);
 }
 
-template <int BN>
+template <int BN, bool RELU>
 __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dw_kernel(const bf16_t* __restrict__ M, int64_t ldm,
                                                                     const float* __restrict__ dH,
                                                                     const float* __restrict__ Zs, int n, int f, int g,
-                                                                    int relu, int slab_rows, float* __restrict__ part) {
+                                                                    int slab_rows, float* __restrict__ part) {
   constexpr int TM = 2, TN = BN / 64;
   constexpr int AI = kWK * (kWM / 8) / kHThreads;   // 8-feature chunks of the M tile per thread (2)
   constexpr int BI = kWK * (BN / 4) / kHThreads;    // 4-column chunks of the dZ tile per thread (4 or 2)
@@ -397,49 +396,44 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dw_kernel(const bf16_t
   const int kbeg = slab * slab_rows, kend = min(n, kbeg + slab_rows);
 
   u32x4 ra[AI];
-  float rb[BI][4];
+  float4 rb[BI], rz[RELU ? BI : 1];
+  // Branch-free loads (rows past the slab's end are clamped to its last row and zeroed when staged); the
+  // ReLU mask and the split are applied at staging, after the current tile's products have been issued.
   auto fetch = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
       const int c = tid + kHThreads * i;
-      const int row = k0 + c / (kWM / 8), col = m0 + (c % (kWM / 8)) * 8;
-      if (row < kend) ra[i] = *reinterpret_cast<const u32x4*>(M + static_cast<int64_t>(row) * ldm + col);
-      else ra[i] = u32x4{0u, 0u, 0u, 0u};
+      const int row = min(k0 + c / (kWM / 8), kend - 1), col = m0 + (c % (kWM / 8)) * 8;
+      ra[i] = *reinterpret_cast<const u32x4*>(M + static_cast<int64_t>(row) * ldm + col);
     }
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
       const int c = tid + kHThreads * i;
-      const int row = k0 + c / (BN / 4), col = n0 + (c % (BN / 4)) * 4;
-      if (row < kend) {
-        const int64_t off = static_cast<int64_t>(row) * g + col;
-        const float4 v = *reinterpret_cast<const float4*>(dH + off);
-        rb[i][0] = v.x; rb[i][1] = v.y; rb[i][2] = v.z; rb[i][3] = v.w;
-        if (relu) {
-          const float4 z = *reinterpret_cast<const float4*>(Zs + off);
-          rb[i][0] = z.x > 0.0f ? rb[i][0] : 0.0f;
-          rb[i][1] = z.y > 0.0f ? rb[i][1] : 0.0f;
-          rb[i][2] = z.z > 0.0f ? rb[i][2] : 0.0f;
-          rb[i][3] = z.w > 0.0f ? rb[i][3] : 0.0f;
-        }
-      } else {
-        rb[i][0] = rb[i][1] = rb[i][2] = rb[i][3] = 0.0f;
-      }
+      const int row = min(k0 + c / (BN / 4), kend - 1), col = n0 + (c % (BN / 4)) * 4;
+      const int64_t off = static_cast<int64_t>(row) * g + col;
+      rb[i] = *reinterpret_cast<const float4*>(dH + off);
+      if (RELU) rz[i] = *reinterpret_cast<const float4*>(Zs + off);
     }
   };
-  auto stage = [&]() {
+  auto stage = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < AI; ++i) {
       const int c = tid + kHThreads * i;
+      const bool in = k0 + c / (kWM / 8) < kend;
       uint2* dst = reinterpret_cast<uint2*>(&As[c / (kWM / 8)][(c % (kWM / 8)) * 8]);   // rows are 8-byte aligned
-      dst[0] = make_uint2(ra[i][0], ra[i][1]);
-      dst[1] = make_uint2(ra[i][2], ra[i][3]);
+      dst[0] = in ? make_uint2(ra[i][0], ra[i][1]) : make_uint2(0u, 0u);
+      dst[1] = in ? make_uint2(ra[i][2], ra[i][3]) : make_uint2(0u, 0u);
     }
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
       const int c = tid + kHThreads * i;
+      const bool in = k0 + c / (BN / 4) < kend;
+      const float4 z = rz[RELU ? i : 0];
+      const float v[4] = {(in && (!RELU || z.x > 0.0f)) ? rb[i].x : 0.0f, (in && (!RELU || z.y > 0.0f)) ? rb[i].y : 0.0f,
+                          (in && (!RELU || z.z > 0.0f)) ? rb[i].z : 0.0f, (in && (!RELU || z.w > 0.0f)) ? rb[i].w : 0.0f};
       uint16_t hi[4], lo[4];
 #pragma unroll
-      for (int j = 0; j < 4; ++j) split_bf16(rb[i][j], hi[j], lo[j]);
+      for (int j = 0; j < 4; ++j) split_bf16(v[j], hi[j], lo[j]);
       const int r = c / (BN / 4), col = (c % (BN / 4)) * 4;
       *reinterpret_cast<uint2*>(&Bh[r][col]) = make_uint2(hi[0] | (static_cast<uint32_t>(hi[1]) << 16),
                                                          hi[2] | (static_cast<uint32_t>(hi[3]) << 16));
@@ -458,7 +452,7 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dw_kernel(const bf16_t
 
   fetch(kbeg);
   for (int k0 = kbeg; k0 < kend; k0 += kWK) {
-    stage();
+    stage(k0);
     __syncthreads();
     if (k0 + kWK < kend) fetch(k0 + kWK);
 #pragma unroll
@@ -512,15 +506,14 @@ int launch_dense_dw_bf16(const void* M, int64_t ldm, const float* dH, const floa
   const int bn = f_out % 128 == 0 ? 128 : 64;
   const int tiles = (f_in / kWM) * (f_out / bn);
   const unsigned grid = static_cast<unsigned>(ceil_div(slabs, 8) * 8 * tiles);
-  if (bn == 128) gemm_bf16_dw_kernel<128><<<grid, kHThreads, 0, st>>>(m, ldm, dH, Zs, n, f_in, f_out, relu, slab_rows, part);
-  else gemm_bf16_dw_kernel<64><<<grid, kHThreads, 0, st>>>(m, ldm, dH, Zs, n, f_in, f_out, relu, slab_rows, part);
+#define CDF_BF16_DW(BNV)                                                                                              \
+  if (relu) gemm_bf16_dw_kernel<BNV, true><<<grid, kHThreads, 0, st>>>(m, ldm, dH, Zs, n, f_in, f_out, slab_rows, part); \
+  else gemm_bf16_dw_kernel<BNV, false><<<grid, kHThreads, 0, st>>>(m, ldm, dH, Zs, n, f_in, f_out, slab_rows, part)
+  if (bn == 128) { CDF_BF16_DW(128); }
+  else { CDF_BF16_DW(64); }
+#undef CDF_BF16_DW
   return CDF_OK;
 }
-
-// Rows from which the forward and dM products take 256-row tiles (a wavefront then holds 4 x 2 tiles of
-// 32 x 32 and reads 0.5 instead of 0.75 LDS operands per matrix instruction): enough row tiles to fill
-// the chip's 512 workgroup slots at two column blocks.
-constexpr int kTallRows = 256 * 512;
 
 bool dense_bwd_bf16_ok(const void* M, const float* W, const float* Zs, const float* dH, int32_t f_out) {
   return f_out % 8 == 0 && aligned(W, 16) && aligned(dH, 16) && (!Zs || aligned(Zs, 16)) && aligned(M, 2);
@@ -530,12 +523,14 @@ int launch_dense_dm_bf16(const float* dH, const float* Zs, const float* W, int32
                          int relu, void* dM, int64_t lddm, hipStream_t st) {
   ProfScope ps(K_GEMM_DM, st);
   const int bn = f_in > 64 ? 128 : 64;
-  const bool tall = bn == 128 && n >= kTallRows;
-  const unsigned grid = xcd_grid(ceil_div(n, tall ? 256 : 128), ceil_div(f_in, bn));
+  const unsigned grid = xcd_grid(ceil_div(n, 128), ceil_div(f_in, bn));
   bf16_t* o = static_cast<bf16_t*>(dM);
-  if (tall) gemm_bf16_dm_kernel<128, 4><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
-  else if (bn == 128) gemm_bf16_dm_kernel<128, 2><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
-  else gemm_bf16_dm_kernel<64, 2><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, relu, o, lddm);
+#define CDF_BF16_DM(BNV)                                                                             \
+  if (relu) gemm_bf16_dm_kernel<BNV, true><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, o, lddm); \
+  else gemm_bf16_dm_kernel<BNV, false><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, o, lddm)
+  if (bn == 128) { CDF_BF16_DM(128); }
+  else { CDF_BF16_DM(64); }
+#undef CDF_BF16_DM
   return CDF_OK;
 }
 
@@ -555,8 +550,7 @@ int launch_dense_fwd_bf16(const void* M, int64_t ldm, const float* W, int32_t n,
   // 128 columns per block at most: the wider tile measured slower (three resident blocks per compute
   // unit hide the barrier and LDS latency of this short pipeline better than one wide block)
   const int bn = f_out > 64 ? 128 : 64;
-  const bool tall = bn == 128 && n >= kTallRows;
-  const unsigned grid = xcd_grid(ceil_div(n, tall ? 256 : 128), ceil_div(f_out, bn));
+  const unsigned grid = xcd_grid(ceil_div(n, 128), ceil_div(f_out, bn));
   const bool pre = ws && aligned(ws, 256) && ws_bytes >= dense_fwd_bf16_workspace_bytes(f_in, f_out);
   uint16_t* wh = static_cast<uint16_t*>(ws);
   uint16_t* wl = pre ? wh + align_up(static_cast<size_t>(f_in) * f_out * 2, 256) / 2 : nullptr;
@@ -565,12 +559,11 @@ int launch_dense_fwd_bf16(const void* M, int64_t ldm, const float* W, int32_t n,
     const dim3 sg(static_cast<unsigned>(ceil_div(f_in, 32)), static_cast<unsigned>(ceil_div(f_out, 32)));
     split_transpose_kernel<<<sg, 256, 0, st>>>(W, f_in, f_out, wh, wl);
   }
-#define CDF_BF16_FWD(BNV, TMV)                                                                                            \
-  if (pre) gemm_bf16_fwd_kernel<BNV, true, TMV><<<grid, kHThreads, 0, st>>>(m, ldm, W, wh, wl, n, f_in, f_out, relu, Z, H); \
-  else gemm_bf16_fwd_kernel<BNV, false, TMV><<<grid, kHThreads, 0, st>>>(m, ldm, W, nullptr, nullptr, n, f_in, f_out, relu, Z, H)
-  if (tall) { CDF_BF16_FWD(128, 4); }
-  else if (bn == 128) { CDF_BF16_FWD(128, 2); }
-  else { CDF_BF16_FWD(64, 2); }
+#define CDF_BF16_FWD(BNV)                                                                                            \
+  if (pre) gemm_bf16_fwd_kernel<BNV, true><<<grid, kHThreads, 0, st>>>(m, ldm, W, wh, wl, n, f_in, f_out, relu, Z, H); \
+  else gemm_bf16_fwd_kernel<BNV, false><<<grid, kHThreads, 0, st>>>(m, ldm, W, nullptr, nullptr, n, f_in, f_out, relu, Z, H)
+  if (bn == 128) { CDF_BF16_FWD(128); }
+  else { CDF_BF16_FWD(64); }
 #undef CDF_BF16_FWD
   return CDF_OK;
 }

@@ -512,9 +512,11 @@ def test_dense_fwd_bwd(cdf, oracle, n, f, g, relu, dtype):
 
 
 @pytest.mark.parametrize("n,f,g", [(131072 + 77, 256, 192), (131072, 128, 128)])
-def test_dense_bf16_tall_tiles(cdf, oracle, n, f, g):
-    """bf16 activations on inputs of 131072 rows and more: the forward and dM products take 256-row
-    tiles there (a ragged last row tile and a half-filled last column block in the first shape)."""
+def test_dense_bf16_many_row_tiles(cdf, oracle, n, f, g):
+    """bf16 activations, more than a thousand row tiles: the 1-D grids of the forward and dM products
+    (row tiles dealt to the XCDs in groups of eight, column blocks of a tile side by side) with a
+    ragged last row tile, a last group of fewer than eight tiles and a half-filled last column block
+    in the first shape."""
     M = features.normal_matrix(17, n + f, n, f).to(torch.bfloat16)
     W = features.glorot(17, g, f, g)
     dH = features.normal_matrix(18, n + g, n, g)
