@@ -56,8 +56,11 @@ __device__ __forceinline__ void load_quad(const T* p, int at, int len, bool vec_
   }
 }
 
-// FAST: every tile is full (no bounds checks) and every operand row is 16-byte aligned
-// (no scalar fall-back); decided on the host.
+// FAST: every operand row is 16-byte aligned and the row widths are multiples of four (no scalar
+// fall-back); decided on the host. Loads then carry no branches: addresses are clamped into the operand
+// (rows and columns past the edge feed outputs that are never stored), reduction elements past the end
+// are zeroed when the tile is staged, and so is the ReLU mask applied, so that nothing waits for a
+// load before the products of the current tile have been issued.
 template <typename T>
 __device__ __forceinline__ void load_quad_fast(const T* p, float (&v)[4]) { VecIO<T, 4>::load(p, v); }
 
@@ -109,8 +112,96 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
 
   float ra[4][4];
   float rb[BQ][4];
+  float rz[FAST && MODE != GEMM_FWD ? (MODE == GEMM_DM ? 4 : BQ) : 1][4];   // Zs beside dH, masked at staging
 
+  auto fetch_fast = [&](int k0) {
+    if (MODE == GEMM_FWD || MODE == GEMM_DM) {
+      // A[m][k] contiguous along k: quad (row = tid/8 + 32 i, k = (tid%8)*4)
+      const int k = min(k0 + (tid & 7) * 4, Kend - 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int m = min(m0 + (tid >> 3) + 32 * i, Mdim - 1);
+        if (MODE == GEMM_FWD) {
+          load_quad_fast<T>(Ap + static_cast<int64_t>(m) * a.lda + k, ra[i]);
+        } else {
+          const int64_t off = static_cast<int64_t>(m) * a.g + k;
+          load_quad_fast<float>(dHp + off, ra[i]);
+          if (a.relu) load_quad_fast<float>(a.mask + off, rz[i]);
+        }
+      }
+    } else {
+      // A[m = feature][k = row] = M[row][feature], contiguous along m: quad (k = tid/32 + 8 i, m = (tid%32)*4)
+      const int m = min(m0 + (tid & 31) * 4, Mdim - 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int k = min(k0 + (tid >> 5) + 8 * i, Kend - 1);
+        load_quad_fast<T>(Ap + static_cast<int64_t>(k) * a.lda + m, ra[i]);
+      }
+    }
+    if (MODE == GEMM_DM) {
+      // B[k = out feature][n = in feature] = W[n][k], contiguous along k: quad (n = tid/8 + 32 i, k = (tid%8)*4)
+      const int k = min(k0 + (tid & 7) * 4, Kend - 4);
+#pragma unroll
+      for (int i = 0; i < BQ; ++i) {
+        const int n = min(n0 + (tid >> 3) + 32 * i, Ndim - 1);
+        load_quad_fast<float>(a.B + static_cast<int64_t>(n) * a.g + k, rb[i]);
+      }
+    } else {
+      // W[k][n] / dZ[k = row][n], contiguous along n: quad (k = tid/(BN/4) + (1024/BN) i, n = (tid % (BN/4)) * 4)
+      const int n = min(n0 + (tid % (BN / 4)) * 4, Ndim - 4);
+#pragma unroll
+      for (int i = 0; i < BQ; ++i) {
+        const int k = min(k0 + tid / (BN / 4) + (1024 / BN) * i, Kend - 1);
+        const int64_t off = static_cast<int64_t>(k) * a.g + n;
+        load_quad_fast<float>(a.B + off, rb[i]);
+        if (MODE == GEMM_DW && a.relu) load_quad_fast<float>(a.mask + off, rz[i]);
+      }
+    }
+  };
+  // FAST: zero what lies past the end of the reduction and apply the ReLU mask, in registers, before staging
+  auto finish_fast = [&](int k0) {
+    if (MODE == GEMM_FWD || MODE == GEMM_DM) {
+      const bool kin = k0 + (tid & 7) * 4 < Kend;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const bool keep = kin && (MODE == GEMM_FWD || !a.relu || rz[MODE == GEMM_DM ? i : 0][c] > 0.0f);
+          ra[i][c] = keep ? ra[i][c] : 0.0f;
+        }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool kin = k0 + (tid >> 5) + 8 * i < Kend;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) ra[i][c] = kin ? ra[i][c] : 0.0f;
+      }
+    }
+    if (MODE == GEMM_DM) {
+      const bool kin = k0 + (tid & 7) * 4 < Kend;
+#pragma unroll
+      for (int i = 0; i < BQ; ++i)
+#pragma unroll
+        for (int c = 0; c < 4; ++c) rb[i][c] = kin ? rb[i][c] : 0.0f;
+    } else {
+#pragma unroll
+      for (int i = 0; i < BQ; ++i) {
+        const bool kin = k0 + tid / (BN / 4) + (1024 / BN) * i < Kend;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+          const bool keep = kin && (MODE != GEMM_DW || !a.relu || rz[MODE == GEMM_DW ? i : 0][c] > 0.0f);
+          rb[i][c] = keep ? rb[i][c] : 0.0f;
+        }
+      }
+    }
+  };
+
+  // general path: bounds checks and scalar fall-backs, the mask applied as the operand is loaded
   auto fetch = [&](int k0) {
+    if (FAST) {
+      fetch_fast(k0);
+      return;
+    }
     // ---- A operand ----
     if (MODE == GEMM_FWD) {
       // M[m][k], contiguous along k: quad (row = tid/8 + 32 i, k = (tid%8)*4)
@@ -118,8 +209,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
       for (int i = 0; i < 4; ++i) {
         const int m = m0 + (tid >> 3) + 32 * i;
         const int k = k0 + (tid & 7) * 4;
-        if (FAST) load_quad_fast<T>(Ap + static_cast<int64_t>(m) * a.lda + k, ra[i]);
-        else if (m < Mdim && k < Kend) load_quad<T>(Ap + static_cast<int64_t>(m) * a.lda + k, k, Kend, a_vec, ra[i]);
+        if (m < Mdim && k < Kend) load_quad<T>(Ap + static_cast<int64_t>(m) * a.lda + k, k, Kend, a_vec, ra[i]);
         else ra[i][0] = ra[i][1] = ra[i][2] = ra[i][3] = 0.0f;
       }
     } else if (MODE == GEMM_DM) {
@@ -128,14 +218,12 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
       for (int i = 0; i < 4; ++i) {
         const int m = m0 + (tid >> 3) + 32 * i;
         const int k = k0 + (tid & 7) * 4;
-        if (FAST || (m < Mdim && k < Kend)) {
+        if (m < Mdim && k < Kend) {
           const int64_t off = static_cast<int64_t>(m) * a.g + k;
-          if (FAST) load_quad_fast<float>(dHp + off, ra[i]);
-          else load_quad<float>(dHp + off, k, Kend, a_vec, ra[i]);
+          load_quad<float>(dHp + off, k, Kend, a_vec, ra[i]);
           if (a.relu) {
             float z[4];
-            if (FAST) load_quad_fast<float>(a.mask + off, z);
-            else load_quad<float>(a.mask + off, k, Kend, m_vec, z);
+            load_quad<float>(a.mask + off, k, Kend, m_vec, z);
 #pragma unroll
             for (int c = 0; c < 4; ++c) ra[i][c] = z[c] > 0.0f ? ra[i][c] : 0.0f;
           }
@@ -147,8 +235,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
       for (int i = 0; i < 4; ++i) {
         const int k = k0 + (tid >> 5) + 8 * i;
         const int m = m0 + (tid & 31) * 4;
-        if (FAST) load_quad_fast<T>(Ap + static_cast<int64_t>(k) * a.lda + m, ra[i]);
-        else if (k < Kend && m < Mdim) load_quad<T>(Ap + static_cast<int64_t>(k) * a.lda + m, m, Mdim, a_vec, ra[i]);
+        if (k < Kend && m < Mdim) load_quad<T>(Ap + static_cast<int64_t>(k) * a.lda + m, m, Mdim, a_vec, ra[i]);
         else ra[i][0] = ra[i][1] = ra[i][2] = ra[i][3] = 0.0f;
       }
     }
@@ -159,8 +246,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
       for (int i = 0; i < BQ; ++i) {
         const int k = k0 + tid / (BN / 4) + (1024 / BN) * i;
         const int n = n0 + (tid % (BN / 4)) * 4;
-        if (FAST) load_quad_fast<float>(a.B + static_cast<int64_t>(k) * a.g + n, rb[i]);
-        else if (k < Kend && n < Ndim) load_quad<float>(a.B + static_cast<int64_t>(k) * a.g + n, n, Ndim, b_vec, rb[i]);
+        if (k < Kend && n < Ndim) load_quad<float>(a.B + static_cast<int64_t>(k) * a.g + n, n, Ndim, b_vec, rb[i]);
         else rb[i][0] = rb[i][1] = rb[i][2] = rb[i][3] = 0.0f;
       }
     } else if (MODE == GEMM_DM) {
@@ -169,8 +255,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
       for (int i = 0; i < BQ; ++i) {
         const int n = n0 + (tid >> 3) + 32 * i;
         const int k = k0 + (tid & 7) * 4;
-        if (FAST) load_quad_fast<float>(a.B + static_cast<int64_t>(n) * a.g + k, rb[i]);
-        else if (n < Ndim && k < Kend) load_quad<float>(a.B + static_cast<int64_t>(n) * a.g + k, k, Kend, b_vec, rb[i]);
+        if (n < Ndim && k < Kend) load_quad<float>(a.B + static_cast<int64_t>(n) * a.g + k, k, Kend, b_vec, rb[i]);
         else rb[i][0] = rb[i][1] = rb[i][2] = rb[i][3] = 0.0f;
       }
     } else {
@@ -179,14 +264,12 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
       for (int i = 0; i < BQ; ++i) {
         const int k = k0 + tid / (BN / 4) + (1024 / BN) * i;
         const int n = n0 + (tid % (BN / 4)) * 4;
-        if (FAST || (k < Kend && n < Ndim)) {
+        if (k < Kend && n < Ndim) {
           const int64_t off = static_cast<int64_t>(k) * a.g + n;
-          if (FAST) load_quad_fast<float>(a.B + off, rb[i]);
-          else load_quad<float>(a.B + off, n, Ndim, b_vec, rb[i]);
+          load_quad<float>(a.B + off, n, Ndim, b_vec, rb[i]);
           if (a.relu) {
             float z[4];
-            if (FAST) load_quad_fast<float>(a.mask + off, z);
-            else load_quad<float>(a.mask + off, n, Ndim, m_vec, z);
+            load_quad<float>(a.mask + off, n, Ndim, m_vec, z);
 #pragma unroll
             for (int c = 0; c < 4; ++c) rb[i][c] = z[c] > 0.0f ? rb[i][c] : 0.0f;
           }
@@ -195,7 +278,8 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
     }
   };
 
-  auto stage = [&]() {
+  auto stage = [&](int k0) {
+    if (FAST) finish_fast(k0);
     if (MODE == GEMM_DW) {
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -231,7 +315,7 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
   const int l32 = lane & 31, lh = lane >> 5;
   if (Kbeg < Kend) fetch(Kbeg);
   for (int k0 = Kbeg; k0 < Kend; k0 += kBK) {
-    stage();
+    stage(k0);
     __syncthreads();
     if (k0 + kBK < Kend) fetch(k0 + kBK);
     // operands of step kk + 2 are read from LDS while the products of step kk run
@@ -266,11 +350,11 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
       const int col = n0 + wn * (BN / 2) + j * 32 + l32;
-      if (!FAST && col >= Ndim) continue;
+      if (col >= Ndim) continue;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int row = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
-        if (!FAST && row >= Mdim) continue;
+        if (row >= Mdim) continue;
         const float v = acc[i][j][e];
         if (MODE == GEMM_FWD) {
           const int64_t off = static_cast<int64_t>(row) * a.g + col;
@@ -335,10 +419,8 @@ static void launch_gemm(const GemmArgs& a, int Mdim, int Ndim, int slabs, int a_
   // wide outputs: 256 columns per block so that the A operand is read once (the slab-split dW
   // product has enough blocks already and runs better on 128)
   const int bn = Ndim > 128 && MODE != GEMM_DW ? 256 : Ndim > 64 ? 128 : 64;
-  // reduction length: f_in (FWD), f_out (DM), rows per slab (DW: every slab must be full)
-  const int Kdim = MODE == GEMM_FWD ? a.f : MODE == GEMM_DM ? a.g : a.slab_rows;
-  const bool k_full = Kdim % kBK == 0 && (MODE != GEMM_DW || a.n % a.slab_rows == 0);
-  const bool fast = Mdim % kBM == 0 && Ndim % bn == 0 && k_full && a_vec && b_vec && (!a.relu || MODE == GEMM_FWD || m_vec);
+  // the branch-free loads need 16-byte aligned rows and widths that are multiples of four, not whole tiles
+  const bool fast = a.f % 4 == 0 && a.g % 4 == 0 && a_vec && b_vec && (!a.relu || MODE == GEMM_FWD || m_vec);
   dim3 grid(static_cast<unsigned>(ceil_div(Mdim, kBM)), static_cast<unsigned>(ceil_div(Ndim, bn)), 1);
   if (MODE == GEMM_DW)   // 1-D: groups of eight slabs, all tiles of a slab on ids that are equal modulo 8
     grid = dim3(static_cast<unsigned>(ceil_div(slabs, 8) * 8 * grid.x * grid.y), 1, 1);

@@ -475,7 +475,10 @@ def test_spmm_dense_fwd_long_and_empty_rows(cdf, oracle):
 
 
 DENSE_SHAPES = [(1000, 100, 47), (300, 602, 256), (513, 16, 8), (700, 128, 256), (257, 256, 41), (130, 64, 64),
-                (5000, 128, 16), (64, 33, 130), (4096, 128, 256), (2048, 256, 64), (1024, 64, 128)]
+                (5000, 128, 16), (64, 33, 130), (4096, 128, 256), (2048, 256, 64), (1024, 64, 128),
+                # aligned rows with ragged tiles: a reduction tail in the forward and dM products, a last
+                # slab of dW that ends inside a tile, fewer columns than a tile
+                (1000, 100, 48), (515, 36, 20), (300, 260, 132)]
 
 
 @pytest.mark.parametrize("n,f,g", DENSE_SHAPES)
