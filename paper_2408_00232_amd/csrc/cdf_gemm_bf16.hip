@@ -351,23 +351,31 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
 // ---- dW = M^T dZ for bf16-stored activations (Sec. 3.1, gradient w.r.t. the weights) ----------------
 // The reduction runs over the rows, along which neither operand is contiguous in memory, while a lane of
 // a 32x32x16 product supplies eight CONSECUTIVE reduction elements of one output row / column. The
-// tiles are therefore kept in LDS in the order they have in memory (As[row][feature], Bh / Bl
-// [row][column], a tile of 32 rows), and a lane assembles its operand from eight 16-bit LDS reads, one
-// per row: the 32 lanes of a half-wavefront read 32 neighbouring features of one row (64 contiguous
-// bytes, no bank conflict), and the row stride is chosen so that the two half-wavefronts, eight rows
-// apart, fall on different banks. M is bf16 and enters unchanged; dZ = dH * [Zs > 0] is fp32 and is
-// split into a bf16 high and low part while it is staged: dW = M^T dZh + M^T dZl, fp32 accumulation.
-// Slabs of rows, partial tiles and their ordered reduction are those of the fp32 kernel.
+// tiles are kept in LDS in the order they have in memory (As[row][feature], Bh / Bl [row][column], a
+// tile of 32 rows) and the operands are read with the transposing LDS load of gfx950
+// (ds_read_b64_tr_b16): the 16 lanes of a group each name 8 bytes - lane p the four features
+// 4 (p % 4) .. + 3 of row p / 4 - and lane j gets back element j % 4 of the blocks of lanes j / 4,
+// 4 + j / 4, 8 + j / 4, 12 + j / 4: feature j of four consecutive rows. Two such loads make the eight
+// reduction elements of a lane. The row stride (80 words) puts the four rows a load touches on
+// disjoint banks. M is bf16 and enters unchanged; dZ = dH * [Zs > 0] is fp32 and is split into a bf16
+// high and low part while it is staged: dW = M^T dZh + M^T dZl, fp32 accumulation. Slabs of rows,
+// partial tiles and their ordered reduction are those of the fp32 kernel.
 constexpr int kWK = 32;            // rows (reduction elements) per LDS tile
 constexpr int kWM = 128;           // features (output rows) per block
-constexpr int kWS = 128 + 4;       // LDS row stride in bf16 elements: 66 words, so 8 rows further is 16 banks further
+constexpr int kWS = 128 + 32;      // LDS row stride in bf16 elements: 80 words, so the next row is 16 banks further
 
-__device__ __forceinline__ bf16x8 gather8(const uint16_t* base, int stride) {
-  // eight elements, one per LDS row, packed in ascending row order
-  u32x4 v;
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-    v[q] = static_cast<uint32_t>(base[(2 * q) * stride]) | (static_cast<uint32_t>(base[(2 * q + 1) * stride]) << 16);
+typedef short short4v __attribute__((ext_vector_type(4)));
+
+// Eight reduction elements (rows k .. k + 7 of the tile) of column col0 + (lane % 32) for lane (l32, lh):
+// `tile` points at row ks of the LDS tile; see the layout of the transposing load above.
+__device__ __forceinline__ bf16x8 read_tr8(const uint16_t* tile, int col0, int lane) {
+  const int grp = lane >> 4, p = lane & 15;
+  const uint16_t* at = tile + ((grp >> 1) * 8 + (p >> 2)) * kWS + col0 + (grp & 1) * 16 + (p & 3) * 4;
+  typedef __attribute__((address_space(3))) short4v* lds_ptr;
+  const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(at));
+  const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(at + 4 * kWS));
+  typedef short short8v __attribute__((ext_vector_type(8)));
+  const short8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   return __builtin_bit_cast(bf16x8, v);
 }
 
@@ -420,9 +428,7 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dw_kernel(const bf16_t
     for (int i = 0; i < AI; ++i) {
       const int c = tid + kHThreads * i;
       const bool in = k0 + c / (kWM / 8) < kend;
-      uint2* dst = reinterpret_cast<uint2*>(&As[c / (kWM / 8)][(c % (kWM / 8)) * 8]);   // rows are 8-byte aligned
-      dst[0] = in ? make_uint2(ra[i][0], ra[i][1]) : make_uint2(0u, 0u);
-      dst[1] = in ? make_uint2(ra[i][2], ra[i][3]) : make_uint2(0u, 0u);
+      *reinterpret_cast<u32x4*>(&As[c / (kWM / 8)][(c % (kWM / 8)) * 8]) = in ? ra[i] : u32x4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int i = 0; i < BI; ++i) {
@@ -460,11 +466,11 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dw_kernel(const bf16_t
       // lane (l32, lh): output row / column l32 of its 32x32 tile, reduction rows ks + lh*8 .. + 7
       bf16x8 a[TM], bh[TN], bl[TN];
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a[i] = gather8(&As[ks + lh * 8][wm * 64 + i * 32 + l32], kWS);
+      for (int i = 0; i < TM; ++i) a[i] = read_tr8(&As[ks][0], wm * 64 + i * 32, lane);
 #pragma unroll
       for (int j = 0; j < TN; ++j) {
-        bh[j] = gather8(&Bh[ks + lh * 8][wn * (BN / 2) + j * 32 + l32], kWS);
-        bl[j] = gather8(&Bl[ks + lh * 8][wn * (BN / 2) + j * 32 + l32], kWS);
+        bh[j] = read_tr8(&Bh[ks][0], wn * (BN / 2) + j * 32, lane);
+        bl[j] = read_tr8(&Bl[ks][0], wn * (BN / 2) + j * 32, lane);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
