@@ -9,6 +9,8 @@
 // the current one is multiplied. The ReLU mask is applied while the dZ operand is loaded,
 // so dZ never exists in memory. dW partial tiles of each row slab go to the workspace
 // and are summed in slab order by a second kernel: no atomics, reproducible.
+#include <type_traits>
+
 #include "cdf_common.h"
 
 namespace cdf {
@@ -345,30 +347,36 @@ __global__ __launch_bounds__(kGemmThreads, 2) void gemm_kernel(GemmArgs a, int a
   }
 
   // ---- epilogue: lane holds column l32 and rows (e/4)*8 + lh*4 + e%4 of each 32x32 tile ----
+  // A workgroup whose tile lies inside the output stores without per-element checks (one uniform branch).
+  auto store_tile = [&](auto checked) {
+    constexpr bool CHECK = decltype(checked)::value;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn * (BN / 2) + j * 32 + l32;
-      if (col >= Ndim) continue;
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * (BN / 2) + j * 32 + l32;
+        if (CHECK && col >= Ndim) continue;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
-        if (row >= Mdim) continue;
-        const float v = acc[i][j][e];
-        if (MODE == GEMM_FWD) {
-          const int64_t off = static_cast<int64_t>(row) * a.g + col;
-          if (a.out0) a.out0[off] = v;
-          if (a.out1) a.out1[off] = a.relu ? (v > 0.0f ? v : 0.0f) : v;
-        } else if (MODE == GEMM_DM) {
-          T* o = static_cast<T*>(a.outT) + static_cast<int64_t>(row) * a.ldo + col;
-          float one[1] = {v};
-          VecIO<T, 1>::store(o, one);
-        } else {
-          a.out0[(static_cast<int64_t>(slab) * a.f + row) * a.g + col] = v;
+        for (int e = 0; e < 16; ++e) {
+          const int row = m0 + wm * 64 + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+          if (CHECK && row >= Mdim) continue;
+          const float v = acc[i][j][e];
+          if (MODE == GEMM_FWD) {
+            const int64_t off = static_cast<int64_t>(row) * a.g + col;
+            if (a.out0) a.out0[off] = v;
+            if (a.out1) a.out1[off] = a.relu ? (v > 0.0f ? v : 0.0f) : v;
+          } else if (MODE == GEMM_DM) {
+            T* o = static_cast<T*>(a.outT) + static_cast<int64_t>(row) * a.ldo + col;
+            float one[1] = {v};
+            VecIO<T, 1>::store(o, one);
+          } else {
+            a.out0[(static_cast<int64_t>(slab) * a.f + row) * a.g + col] = v;
+          }
         }
       }
-    }
+  };
+  if (m0 + kBM <= Mdim && n0 + BN <= Ndim) store_tile(std::false_type{});
+  else store_tile(std::true_type{});
 }
 
 // dW[i] = sum over slabs in a fixed order: four interleaved running sums (slab k goes to sum

@@ -8,6 +8,8 @@
 // that a lane reads its eight consecutive k values of a 32x32x16 operand with one 16-byte access. The next
 // k-tile is fetched into registers while the current one is multiplied. The column blocks of a row tile
 // run on one XCD at the same time (1-D grid, see xcd_tile), so the row tile's operand comes from memory once.
+#include <type_traits>
+
 #include "cdf_common.h"
 
 namespace cdf {
@@ -190,23 +192,29 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
     __syncthreads();
   }
 
-  // lane holds column l32 and rows (e/4)*8 + lh*4 + e%4 of each 32x32 tile
+  // lane holds column l32 and rows (e/4)*8 + lh*4 + e%4 of each 32x32 tile; a tile that lies inside the
+  // output is stored without per-element checks
+  auto store_tile = [&](auto checked) {
+    constexpr bool CHECK = decltype(checked)::value;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn * (BN / 2) + j * 32 + l32;
-      if (col >= g) continue;
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * (BN / 2) + j * 32 + l32;
+        if (CHECK && col >= g) continue;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * (HM / 2) + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
-        if (row >= n) continue;
-        const float v = acc[i][j][e];
-        const int64_t off = static_cast<int64_t>(row) * g + col;
-        if (Z) Z[off] = v;
-        if (H) H[off] = relu ? (v > 0.0f ? v : 0.0f) : v;
+        for (int e = 0; e < 16; ++e) {
+          const int row = m0 + wm * (HM / 2) + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+          if (CHECK && row >= n) continue;
+          const float v = acc[i][j][e];
+          const int64_t off = static_cast<int64_t>(row) * g + col;
+          if (Z) Z[off] = v;
+          if (H) H[off] = relu ? (v > 0.0f ? v : 0.0f) : v;
+        }
       }
-    }
+  };
+  if (m0 + HM <= n && n0 + BN <= g) store_tile(std::false_type{});
+  else store_tile(std::true_type{});
 }
 
 // ---- dM = dZ W^T for bf16-stored activations (Sec. 3.1, gradient w.r.t. the layer input) --------
@@ -332,20 +340,25 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
     }
     __syncthreads();
   }
+  auto store_tile = [&](auto checked) {
+    constexpr bool CHECK = decltype(checked)::value;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn * (BN / 2) + j * 32 + l32;
-      if (col >= f) continue;
+      for (int j = 0; j < TN; ++j) {
+        const int col = n0 + wn * (BN / 2) + j * 32 + l32;
+        if (CHECK && col >= f) continue;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = m0 + wm * (HM / 2) + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
-        if (row >= n) continue;
-        float one[1] = {acc[i][j][e]};
-        VecIO<bf16_t, 1>::store(dM + static_cast<int64_t>(row) * ldo + col, one);
+        for (int e = 0; e < 16; ++e) {
+          const int row = m0 + wm * (HM / 2) + i * 32 + (e >> 2) * 8 + lh * 4 + (e & 3);
+          if (CHECK && row >= n) continue;
+          float one[1] = {acc[i][j][e]};
+          VecIO<bf16_t, 1>::store(dM + static_cast<int64_t>(row) * ldo + col, one);
+        }
       }
-    }
+  };
+  if (m0 + HM <= n && n0 + BN <= f) store_tile(std::false_type{});
+  else store_tile(std::true_type{});
 }
 
 // ---- dW = M^T dZ for bf16-stored activations (Sec. 3.1, gradient w.r.t. the weights) ----------------
