@@ -452,7 +452,7 @@ int launch_dense_fwd_bf16(const void* M, int64_t ldm, const float* W, int32_t n,
                           float* Z, float* H, void* ws, size_t ws_bytes, hipStream_t st);
 bool dense_bwd_bf16_ok(const void* M, const float* W, const float* Zs, const float* dH, int32_t f_out);
 int launch_dense_dm_bf16(const float* dH, const float* Zs, const float* W, int32_t n, int32_t f_in, int32_t f_out,
-                         int relu, void* dM, int64_t lddm, hipStream_t st);
+                         int relu, void* dM, int64_t lddm, void* ws, size_t ws_bytes, hipStream_t st);
 bool dense_dw_bf16_ok(const void* M, int64_t ldm, const float* Zs, const float* dH, int32_t f_in, int32_t f_out);
 int launch_dense_dw_bf16(const void* M, int64_t ldm, const float* dH, const float* Zs, int32_t n, int32_t f_in,
                          int32_t f_out, int relu, int slab_rows, int slabs, float* part, hipStream_t st);
@@ -538,7 +538,8 @@ extern "C" int cdf_dense_bwd(const void* M, int64_t ldm, cdf_dtype dt, const flo
     a.relu = relu ? 1 : 0;
     const int av = vec4(dH, f_out, 4), bv = vec4(W, f_out, 4), mv = relu ? vec4(Zs, f_out, 4) : 0;
     if (dt == CDF_F32) launch_gemm<float, GEMM_DM>(a, n, f_in, 1, av, bv, mv, st);
-    else if (bf16_cores) launch_dense_dm_bf16(dH, Zs, W, n, f_in, f_out, relu ? 1 : 0, dM, lddm, st);
+    // (the workspace is free again: the slab partials of dW have been reduced on this stream)
+    else if (bf16_cores) launch_dense_dm_bf16(dH, Zs, W, n, f_in, f_out, relu ? 1 : 0, dM, lddm, ws, ws_bytes, st);
     else launch_gemm<bf16_t, GEMM_DM>(a, n, f_in, 1, av, bv, mv, st);
     CDF_LAUNCH_CHECK("cdf_dense_bwd/dM");
   }

@@ -57,6 +57,27 @@ __global__ __launch_bounds__(256) void split_transpose_kernel(const float* __res
 
 // PRE: Wh / Wl hold the split, transposed weight (see above) and W is unused; otherwise every block
 // splits its own part of W while staging it.
+// W [count] fp32 -> Wh, Wl [count] bf16 in the same order (count a multiple of 8): the weight operand of
+// dM = dZ W^T, whose reduction index is already contiguous in W.
+__global__ __launch_bounds__(256) void split_kernel(const float* __restrict__ W, int64_t count,
+                                                    uint16_t* __restrict__ Wh, uint16_t* __restrict__ Wl) {
+  const int64_t i = (static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x) * 8;
+  if (i >= count) return;
+  const float4 a = *reinterpret_cast<const float4*>(W + i), b = *reinterpret_cast<const float4*>(W + i + 4);
+  const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+  uint16_t hi[8], lo[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) split_bf16(v[j], hi[j], lo[j]);
+  u32x4 ph, pl;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    ph[q] = static_cast<uint32_t>(hi[2 * q]) | (static_cast<uint32_t>(hi[2 * q + 1]) << 16);
+    pl[q] = static_cast<uint32_t>(lo[2 * q]) | (static_cast<uint32_t>(lo[2 * q + 1]) << 16);
+  }
+  *reinterpret_cast<u32x4*>(Wh + i) = ph;
+  *reinterpret_cast<u32x4*>(Wl + i) = pl;
+}
+
 // Output tile of a workgroup in a 1-D grid of 8 * ceil(row_tiles / 8) * col_blocks workgroups. Workgroups are
 // handed to the 8 XCDs in turn, so workgroup b runs on XCD b mod 8; the column blocks of one row tile get
 // consecutive slots of ONE XCD, run there at the same time and read the row tile's operand once into that
@@ -222,10 +243,12 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_fwd_kernel(const bf16_
 // features), so each is split into bf16 high / low parts while it is staged:
 //   dM = dZh Wh^T + dZh Wl^T + dZl Wh^T          (the low x low term is below 2^-16 of the result)
 // The result is stored as bf16, which is the type the aggregation that follows reads.
-template <int BN, bool RELU>
+template <int BN, bool RELU, bool PRE>
 __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float* __restrict__ dH,
                                                                     const float* __restrict__ Zs,
-                                                                    const float* __restrict__ W, int n, int f, int g,
+                                                                    const float* __restrict__ W,
+                                                                    const uint16_t* __restrict__ Wh,
+                                                                    const uint16_t* __restrict__ Wl, int n, int f, int g,
                                                                     bf16_t* __restrict__ dM, int64_t ldo) {
   constexpr int TM = 2, TN = BN / 64;
   constexpr int HM = 64 * TM;
@@ -242,7 +265,8 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
   if (!xcd_tile((n + HM - 1) / HM, (f + BN - 1) / BN, row_tile, col_block)) return;
   const int m0 = row_tile * HM, n0 = col_block * BN;
 
-  float ra[AI][8], rz[RELU ? AI : 1][8], rb[BI][8];
+  float ra[AI][8], rz[RELU ? AI : 1][8], rb[PRE ? 1 : BI][8];
+  u32x4 rh[PRE ? BI : 1], rl[PRE ? BI : 1];   // W already split (by split_kernel) when the caller has workspace
   auto load8 = [](const float* p, float (&v)[8]) {
     const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
     v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
@@ -253,6 +277,8 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
   const float* dHt = dH + static_cast<int64_t>(m0) * g;
   const float* Zt = RELU ? Zs + static_cast<int64_t>(m0) * g : nullptr;
   const float* Wt = W + static_cast<int64_t>(n0) * g;
+  const uint16_t* Wht = PRE ? Wh + static_cast<int64_t>(n0) * g : nullptr;
+  const uint16_t* Wlt = PRE ? Wl + static_cast<int64_t>(n0) * g : nullptr;
   const int kk = (tid % (kHK / 8)) * 8;   // the thread's k block inside a tile, the same for all its items
   uint32_t arow[AI], brow[BI];
 #pragma unroll
@@ -267,7 +293,14 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
       if (RELU) load8(Zt + (arow[i] + k), rz[i]);
     }
 #pragma unroll
-    for (int i = 0; i < BI; ++i) load8(Wt + (brow[i] + k), rb[i]);
+    for (int i = 0; i < BI; ++i) {
+      if (PRE) {
+        rh[i] = *reinterpret_cast<const u32x4*>(Wht + (brow[i] + k));
+        rl[i] = *reinterpret_cast<const u32x4*>(Wlt + (brow[i] + k));
+      } else {
+        load8(Wt + (brow[i] + k), rb[i]);
+      }
+    }
   };
   auto put = [](const float (&v)[8], uint16_t* hi_dst, uint16_t* lo_dst) {
     uint16_t hi[8], lo[8];
@@ -296,9 +329,14 @@ __global__ __launch_bounds__(kHThreads, 2) void gemm_bf16_dm_kernel(const float*
     for (int i = 0; i < BI; ++i) {
       const int item = tid + kHThreads * i;
       const bool kin = k0 + (item % (kHK / 8)) * 8 < g;
+      if (PRE) {
+        *reinterpret_cast<u32x4*>(&Bh[item / (kHK / 8)][(item % (kHK / 8)) * 8]) = kin ? rh[i] : u32x4{0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4*>(&Bl[item / (kHK / 8)][(item % (kHK / 8)) * 8]) = kin ? rl[i] : u32x4{0u, 0u, 0u, 0u};
+        continue;
+      }
       float v[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) v[j] = kin ? rb[i][j] : 0.0f;
+      for (int j = 0; j < 8; ++j) v[j] = kin ? rb[PRE ? 0 : i][j] : 0.0f;
       put(v, &Bh[item / (kHK / 8)][(item % (kHK / 8)) * 8], &Bl[item / (kHK / 8)][(item % (kHK / 8)) * 8]);
     }
   };
@@ -539,17 +577,28 @@ bool dense_bwd_bf16_ok(const void* M, const float* W, const float* Zs, const flo
 }
 
 int launch_dense_dm_bf16(const float* dH, const float* Zs, const float* W, int32_t n, int32_t f_in, int32_t f_out,
-                         int relu, void* dM, int64_t lddm, hipStream_t st) {
+                         int relu, void* dM, int64_t lddm, void* ws, size_t ws_bytes, hipStream_t st) {
   ProfScope ps(K_GEMM_DM, st);
   const int bn = f_in > 64 ? 128 : 64;
   const unsigned grid = xcd_grid(ceil_div(n, 128), ceil_div(f_in, bn));
   bf16_t* o = static_cast<bf16_t*>(dM);
-#define CDF_BF16_DM(BNV)                                                                             \
-  if (relu) gemm_bf16_dm_kernel<BNV, true><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, o, lddm); \
-  else gemm_bf16_dm_kernel<BNV, false><<<grid, kHThreads, 0, st>>>(dH, Zs, W, n, f_in, f_out, o, lddm)
+  // with workspace the weight is split once (same layout as W) instead of in every block
+  const int64_t count = static_cast<int64_t>(f_in) * f_out;
+  const size_t half = align_up(static_cast<size_t>(count) * 2, 256);
+  const bool pre = ws && aligned(ws, 256) && ws_bytes >= 2 * half;
+  uint16_t* wh = static_cast<uint16_t*>(ws);
+  uint16_t* wl = pre ? wh + half / 2 : nullptr;
+  if (pre) split_kernel<<<static_cast<unsigned>(ceil_div(count, 8 * 256)), 256, 0, st>>>(W, count, wh, wl);
+#define CDF_BF16_DM2(BNV, RELUV)                                                                                   \
+  if (pre) gemm_bf16_dm_kernel<BNV, RELUV, true><<<grid, kHThreads, 0, st>>>(dH, Zs, W, wh, wl, n, f_in, f_out, o, lddm); \
+  else gemm_bf16_dm_kernel<BNV, RELUV, false><<<grid, kHThreads, 0, st>>>(dH, Zs, W, nullptr, nullptr, n, f_in, f_out, o, lddm)
+#define CDF_BF16_DM(BNV)                \
+  if (relu) { CDF_BF16_DM2(BNV, true); } \
+  else { CDF_BF16_DM2(BNV, false); }
   if (bn == 128) { CDF_BF16_DM(128); }
   else { CDF_BF16_DM(64); }
 #undef CDF_BF16_DM
+#undef CDF_BF16_DM2
   return CDF_OK;
 }
 

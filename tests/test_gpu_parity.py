@@ -542,6 +542,32 @@ def test_dense_bf16_many_row_tiles(cdf, oracle, n, f, g):
     assert_bf16_close(to_np(dM), odM, "dM")
 
 
+@pytest.mark.parametrize("n,f,g", [(200, 40, 8), (200, 136, 8)])
+def test_dense_bwd_bf16_weight_split_in_block_or_beforehand(cdf, oracle, n, f, g):
+    """bf16 activations: with room in the workspace dM's weight operand is split into its bf16 parts once,
+    otherwise in every workgroup. A workspace of exactly the slab partials (f*g*4 bytes here, less than
+    the two split copies need after their 256-byte rounding) takes the second route; both give the same
+    bits and match the oracle."""
+    M = features.normal_matrix(27, n + f, n, f).to(torch.bfloat16)
+    W = features.glorot(27, g, f, g)
+    dH = features.normal_matrix(28, n + g, n, g)
+    oZ, _ = oracle.dense_fwd(to_np(M), W.numpy(), True)
+    M_, dH_, W_, Zs = M.to(DEV), dH.to(DEV), W.to(DEV), torch.from_numpy(oZ).to(DEV)
+    outs = []
+    for ws in (ws_for(cdf, n, max(f, g)), torch.zeros(f * g * 4, dtype=torch.uint8, device=DEV)):
+        assert ws.numel() % 256 == 0
+        dW = torch.zeros(f, g, device=DEV)
+        dM = torch.zeros(n, f, dtype=torch.bfloat16, device=DEV)
+        cdf.cdf_dense_bwd(M_, W_, Zs, dH_, True, dW, dM, ws)
+        torch.cuda.synchronize()
+        outs.append((dW, dM))
+    assert 2 * ((f * g * 2 + 255) // 256 * 256) > f * g * 4      # the small workspace cannot hold the split copies
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    odW, odM = oracle.dense_bwd(to_np(M), W.numpy(), oZ, dH.numpy(), True)
+    assert_rows_close(to_np(outs[1][0]), odW, what="dW")
+    assert_bf16_close(to_np(outs[1][1]), odM, "dM")
+
+
 def lockstep_messages(oracle, rows, cache0, L, h, eps, norm, bits, qs, commit, delta):
     """The cache test and the message build of a backward step, redone by the oracle on the halo gradient
     rows the GPU step itself produced (`rows`) against the cache the step started from (`cache0`): mask,
