@@ -7,6 +7,7 @@ profiles/: `layer_step_<workload>.md` (kernel times, memory counters, matrix-cor
 
 expects under --dir one folder per run, named as in `commands()` below: kt (kernel trace), FETCH_SIZE,
 WRITE_SIZE, TCC_HIT_sum, SQ_VALU_MFMA_BUSY_CYCLES (optional). Raw output stays where it is.
+`--sq` summarises one more run (SQ_WAVE_CYCLES: eight wave-level counters) into `sq_counters_<workload>.md`.
 """
 import argparse
 import collections
@@ -30,6 +31,49 @@ def commands(workload, order, d):
         out.append(f"rocprofv3 --pmc {c} --output-format csv -d {d}/{c.split()[0]} -o {workload} -- "
                    f"{common} --steps 2 --warmup 1 --copy-calibration")
     return out
+
+
+SQ_COUNTERS = ("SQ_WAVE_CYCLES SQ_WAIT_ANY SQ_WAIT_INST_ANY SQ_ACTIVE_INST_ANY SQ_ACTIVE_INST_LDS SQ_LDS_BANK_CONFLICT "
+               "SQ_VALU_MFMA_BUSY_CYCLES SQ_BUSY_CYCLES")
+
+
+def sq_command(workload, order, d):
+    """The rocprofv3 run behind `sq_counters_<workload>.md` (eight SQ counters: one pass)."""
+    return (f"rocprofv3 --pmc {SQ_COUNTERS} --output-format csv -d {d}/SQ_WAVE_CYCLES -o {workload} -- "
+            f"python3 bench.py --workload {workload} --order {order} --no-cpu-baseline --no-optimised --no-rho-sweep "
+            f"--epochs 0 --steps 2 --warmup 1")
+
+
+def summarise_sq(workload, order, d, out_dir):
+    """Wave-level counters per kernel: residency, how the waves' time splits, LDS activity."""
+    S = counters(d, "SQ_WAVE_CYCLES", workload)
+    sha = build.sources_sha()
+    L = [f"# rocprofv3 SQ counters: workload `{workload}`, order `{order}` (one MI355X)\n",
+         f"Library sources `{sha}` (paper_2408_00232_amd.build.sources_sha).\n",
+         "Command (from the repository root, `export TMPDIR=/tmp`; summary by "
+         f"`python -m paper_2408_00232_amd.profsum --sq --workload {workload} --order {order} --dir {d}`):\n",
+         "```", sq_command(workload, order, d), "```\n",
+         "Per-launch averages. SQ_BUSY_CYCLES is summed over the 32 shader engines (kernel cycles = value / 32); "
+         "SQ_WAVE_CYCLES, SQ_WAIT_* and SQ_ACTIVE_* are summed over wavefronts in units of 4 cycles; waves / SIMD = "
+         "4 x SQ_WAVE_CYCLES / kernel cycles / 1024 SIMDs; MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (1024 x kernel "
+         "cycles).\n",
+         "| kernel | launches | kernel Mcycles | waves / SIMD | MFMA busy % | wait-any % of wave time | wait-issue % | "
+         "LDS active (M quad-cycles) | LDS bank conflict (M) |", "|---|---:|---:|---:|---:|---:|---:|---:|---:|"]
+    for k, c in S.items():
+        if "cdf::" not in k:
+            continue
+        av = {n: mean(v) for n, v in c.items()}
+        cyc = av["SQ_BUSY_CYCLES"] / 32
+        wave = max(av["SQ_WAVE_CYCLES"], 1.0)
+        L.append("| `%s` | %d | %.2f | %.2f | %.1f | %.1f | %.1f | %.1f | %.1f |" % (
+            k, len(c["SQ_BUSY_CYCLES"]), cyc / 1e6, 4 * av["SQ_WAVE_CYCLES"] / max(cyc, 1.0) / 1024,
+            100 * av["SQ_VALU_MFMA_BUSY_CYCLES"] / (1024 * max(cyc, 1.0)), 100 * av["SQ_WAIT_ANY"] / wave,
+            100 * av["SQ_WAIT_INST_ANY"] / wave, av["SQ_ACTIVE_INST_LDS"] / 1e6, av["SQ_LDS_BANK_CONFLICT"] / 1e6))
+    os.makedirs(out_dir, exist_ok=True)
+    path = os.path.join(out_dir, f"sq_counters_{workload}.md")
+    with open(path, "w") as fh:
+        fh.write("\n".join(L) + "\n")
+    return path
 
 
 def short(name):
@@ -147,9 +191,13 @@ def main(argv=None):
     ap.add_argument("--dir", required=True, help="folder that holds the rocprofv3 output folders")
     ap.add_argument("--out", default=os.path.join(ROOT, "profiles"))
     ap.add_argument("--print-commands", action="store_true")
+    ap.add_argument("--sq", action="store_true", help="summarise the SQ counter run (sq_counters_<workload>.md) instead")
     args = ap.parse_args(argv)
     if args.print_commands:
-        print("\n".join(commands(args.workload, args.order, args.dir)))
+        print("\n".join(commands(args.workload, args.order, args.dir) + [sq_command(args.workload, args.order, args.dir)]))
+        return
+    if args.sq:
+        print(open(summarise_sq(args.workload, args.order, args.dir, args.out)).read())
         return
     print(open(summarise(args.workload, args.order, args.dir, args.out)).read())
 
